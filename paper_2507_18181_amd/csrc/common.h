@@ -1,0 +1,97 @@
+// Shared device helpers and internal layouts of the tree-verification library (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace specasr {
+
+constexpr int kWave = 64;
+
+// ---- storage types -------------------------------------------------------
+struct bf16_t {
+  uint16_t bits;
+};
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v.bits) << 16); }
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// float -> bf16, round to nearest even (finite inputs; NaN keeps a quiet-NaN pattern)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <class T> __device__ __forceinline__ T from_f32(float f);
+template <> __device__ __forceinline__ float from_f32<float>(float f) { return f; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float f) {
+  bf16_t r;
+  r.bits = f32_to_bf16_bits(f);
+  return r;
+}
+
+// ---- per-call tree metadata as the kernels see it ------------------------
+// Rows are the tree nodes of all sequences of the call, flattened without
+// padding: row = row_start[seq] + node.
+struct StepMeta {
+  const int32_t *token;      // [rows] token id (ignored where use_embed)
+  const int32_t *seq;        // [rows] sequence of the row
+  const int32_t *node;       // [rows] node index inside its tree
+  const int32_t *depth;      // [rows]
+  const int32_t *pos;        // [rows] kv_len[seq] + depth  (rotary position)
+  const int32_t *slot;       // [rows] kv_len[seq] + node   (cache slot)
+  const int32_t *parent;     // [rows] parent node index inside the tree, -1 for the root
+  const int32_t *use_embed;  // [rows]
+  const uint64_t *anc;       // [rows] bit j set iff node j is on the row's root path (self included)
+  const int32_t *kv_len;     // [batch]
+  const int32_t *row_start;  // [batch]
+  const int32_t *n_nodes;    // [batch]
+  int32_t rows, batch;
+};
+
+// KV cache geometry: element index of (seq, layer, kv head, slot, 0)
+struct KvGeom {
+  int64_t capacity;
+  int32_t n_layers, n_kv_heads, head_dim;
+  __host__ __device__ int64_t row(int32_t seq, int32_t layer, int32_t h, int64_t slot) const {
+    return ((((int64_t)seq * n_layers + layer) * n_kv_heads + h) * capacity + slot) * head_dim;
+  }
+};
+
+// ---- wavefront / block reductions ---------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Block-wide reductions for blockDim.x a multiple of 64 and <= 1024. `red` holds >= 16 floats.
+__device__ __forceinline__ float block_sum(float v, float *red) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  float t = 0.f;
+  for (int i = 0; i < nw; ++i) t += red[i];
+  return t;
+}
+__device__ __forceinline__ float block_max(float v, float *red) {
+  v = wave_max(v);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  float t = red[0];
+  for (int i = 1; i < nw; ++i) t = fmaxf(t, red[i]);
+  return t;
+}
+
+}  // namespace specasr

@@ -1,0 +1,318 @@
+"""GPU parity on the tiny model: HIP path (through the C ABI) vs the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import form_s
+import workload as wl
+from parity_util import (TOL_F32, TOL_BF16, check_forward, check_tree_kv, oracle_prefilled,
+                         row_rel_err, widen_cache, walk_is_decisive)
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _verifier(*a, **k):
+    from paper_2507_18181_amd.runtime import Verifier
+    return Verifier(*a, **k)
+
+
+def _cfg1(dtype="f32"):
+    spec = wl.WORKLOADS["cfg1_tiny"]
+    cfg = wl.MODELS["tiny"]
+    w = wl.make_weights(cfg, spec["seed"], dtype)
+    audio, text = wl.make_prefix_inputs(cfg, spec["seed"], spec["n_audio"], spec["n_text"])
+    parents, tokens = wl.make_tree("cfg1_tiny")
+    return cfg, w, audio, text, parents, tokens
+
+
+def _store_cache(kc, dtype):
+    a = kc[None].astype(np.float32)
+    return wl.bf16_bits(a) if dtype == "bf16" else a
+
+
+@pytest.mark.parametrize("dtype,flags,tol", [("f32", 0, TOL_F32), ("bf16", 1, TOL_BF16),
+                                             ("bf16", 0, TOL_BF16)])
+def test_cfg1_forward_and_round(dtype, flags, tol):
+    """Tiny workload: 2 layers, d 256, 4 heads, FFN 688, vocab 1000; prefix 48 audio + 16 text;
+    8-node tree with a branch.  fp32 model at 1e-4; bf16-rounded model at 2e-2."""
+    cfg, w, audio, text, parents, tokens = _cfg1(dtype)
+    om, kc, vc, L, _ = oracle_prefilled(cfg, w, audio, text, 96)
+    ver = _verifier(cfg, w, dtype, max_nodes=8, capacity=96, flags=flags)
+    ver.set_cache(_store_cache(kc, dtype), _store_cache(vc, dtype), [L])
+    k0, v0 = ver.get_cache()
+    ref = om.tree_forward(k0[0], v0[0], L, tokens, parents)       # oracle reads the GPU's cache bits
+
+    fw = ver.tree_forward([tokens], [parents])
+    assert fw["status"] == 0
+    check_forward(ref, fw["logits"][0].cpu().numpy(), fw["argmax"][0].cpu().numpy(), tol)
+    k1, v1 = ver.get_cache()
+    check_tree_kv(k1[0], v1[0], L, ref, tol)
+    assert np.array_equal(k1[:, :, :, :L], k0[:, :, :, :L]) and np.array_equal(v1[:, :, :, :L], v0[:, :, :, :L])
+    assert ver.kv_len[0] == L
+
+    out = ver.verify_tree([tokens], [parents], want_logits=True)
+    assert out["status"] == 0
+    n = len(parents)
+    path, alen, nxt = oracle.accept(tokens, parents, out["argmax"][0, :n])   # integer stage, same argmax
+    assert out["accept_len"][0] == alen and out["next_token"][0] == nxt
+    assert out["path"][0, :alen].tolist() == path.tolist() and np.all(out["path"][0, alen:] == -1)
+    assert ver.kv_len[0] == L + alen
+    k2, v2 = ver.get_cache()
+    for k in range(alen):     # compaction is a byte move of the rows computed by the forward
+        assert np.array_equal(k2[0, :, :, L + k], k1[0, :, :, L + path[k]])
+        assert np.array_equal(v2[0, :, :, L + k], v1[0, :, :, L + path[k]])
+    assert np.array_equal(k2[:, :, :, :L], k0[:, :, :, :L])
+    ver.close()
+
+
+@pytest.mark.parametrize("dtype,tol", [("f32", TOL_F32), ("bf16", TOL_BF16)])
+def test_planted_drafts_sweep_accept_len_and_take_the_branch(dtype, tol):
+    """Draft tokens follow the oracle's own greedy continuation for k steps, so accept_len sweeps
+    1..6 on the trunk; then the branch carries the right continuation and is taken."""
+    cfg, w, audio, text, parents, tokens = _cfg1(dtype)
+    om, kc, vc, L, _ = oracle_prefilled(cfg, w, audio, text, 96)
+    rows = np.concatenate([audio.astype(np.float64), form_s.widen(w["tok_embed"])[text]])
+    greedy = form_s.greedy_decode(cfg, w, rows, tokens[0], 7)
+    ver = _verifier(cfg, w, dtype, max_nodes=8, capacity=96)
+    cases = []
+    for k in range(6):                   # trunk matches k drafts
+        t = tokens.copy()
+        t[1:1 + k] = greedy[:k]
+        for i in range(1 + k, 6):
+            t[i] = (greedy[i - 1] + 1 + i) % cfg["vocab"]
+        t[6] = (greedy[2] + 1) % cfg["vocab"]
+        cases.append((t, k + 1))
+    t = tokens.copy()                    # trunk right for 2 drafts, branch right for 2 more
+    t[1:3] = greedy[:2]
+    t[3] = (greedy[2] + 1) % cfg["vocab"]
+    t[6], t[7] = greedy[2], greedy[3]
+    cases.append((t, 5))
+    for t, want_len in cases:
+        ver.set_cache(_store_cache(kc, dtype), _store_cache(vc, dtype), [L])
+        k0, v0 = ver.get_cache()
+        ref = om.tree_forward(k0[0], v0[0], L, t, parents)
+        rpath, rlen, rnext = oracle.accept(t, parents, ref["amax"])
+        out = ver.verify_tree([t], [parents], want_logits=True)
+        assert out["status"] == 0
+        check_forward(ref, out["logits"][0].cpu().numpy(), out["argmax"][0], tol)
+        if walk_is_decisive(ref["logits"], t, parents, rpath, rlen):
+            assert out["accept_len"][0] == rlen and out["next_token"][0] == rnext
+            assert out["path"][0, :rlen].tolist() == rpath.tolist()
+            if dtype == "f32":
+                assert rlen == want_len
+        k2, v2 = ver.get_cache()
+        alen = int(out["accept_len"][0])
+        got_k = widen_cache(k2[0, :, :, L:L + alen])
+        want_k = ref["ktree"][:, :, out["path"][0, :alen]]
+        assert np.abs(got_k - want_k).max() <= tol * np.abs(want_k).max()
+    ver.close()
+
+
+@pytest.mark.parametrize("dtype,tol,flags", [("f32", TOL_F32, 0), ("bf16", TOL_BF16, 0),
+                                             ("bf16", TOL_BF16, 1)])
+def test_random_trees_all_sizes(dtype, tol, flags):
+    """Ragged tree sizes 1..64 (several 16-row tiles and tails), random shapes, varying kv_len."""
+    cfg = wl.MODELS["tiny"]
+    w = wl.make_weights(cfg, 77, dtype)
+    rng = np.random.default_rng(78)
+    audio = rng.standard_normal((40, cfg["d_model"])).astype(np.float32)
+    text = rng.integers(0, cfg["vocab"], 300).astype(np.int32)
+    om, kc, vc, Lfull, _ = oracle_prefilled(cfg, w, audio, text, 420)
+    ver = _verifier(cfg, w, dtype, max_nodes=64, capacity=420, flags=flags)
+    for n, L in ((1, 0), (1, 5), (2, 64), (7, 63), (15, 255), (16, 256), (17, 257), (33, 100),
+                 (48, 340), (63, 129), (64, 340)):
+        parents = wl.random_tree(rng, n, max_children=3)
+        tokens = rng.integers(0, cfg["vocab"], n).astype(np.int32)
+        ver.set_cache(_store_cache(kc, dtype), _store_cache(vc, dtype), [L])
+        k0, v0 = ver.get_cache()
+        ref = om.tree_forward(k0[0], v0[0], L, tokens, parents)
+        fw = ver.tree_forward([tokens], [parents])
+        assert fw["status"] == 0
+        check_forward(ref, fw["logits"][0].cpu().numpy(), fw["argmax"][0].cpu().numpy(), tol)
+        k1, v1 = ver.get_cache()
+        check_tree_kv(k1[0], v1[0], L, ref, tol)
+    ver.close()
+
+
+def test_batch_of_ragged_sequences():
+    """Three sequences with different prefix lengths and trees in one call: each equals the
+    oracle run on it alone."""
+    cfg = wl.MODELS["tiny"]
+    w = wl.make_weights(cfg, 79, "f32")
+    rng = np.random.default_rng(80)
+    ver = _verifier(cfg, w, "f32", max_nodes=16, capacity=128, max_batch=3)
+    om = oracle.OracleModel(cfg, w)
+    caches, Ls = [], [37, 90, 5]
+    K = np.zeros((3, cfg["n_layers"], cfg["n_kv_heads"], 128, cfg["head_dim"]), np.float32)
+    V = np.zeros_like(K)
+    for b, L in enumerate(Ls):
+        kc, vc = om.empty_cache(128)
+        om.prefill(kc, vc, 0, None, rng.integers(0, cfg["vocab"], L).astype(np.int32))
+        K[b], V[b] = kc, vc
+    ver.set_cache(K, V, Ls)
+    k0, v0 = ver.get_cache()
+    trees = [wl.random_tree(rng, n) for n in (16, 3, 9)]
+    toks = [rng.integers(0, cfg["vocab"], len(p)).astype(np.int32) for p in trees]
+    out = ver.verify_tree(toks, trees, want_logits=True)
+    assert out["status"] == 0
+    k2, v2 = ver.get_cache()
+    for b in range(3):
+        ref = om.tree_forward(k0[b], v0[b], Ls[b], toks[b], trees[b])
+        n = len(trees[b])
+        check_forward(ref, out["logits"][b].cpu().numpy(), out["argmax"][b], TOL_F32)
+        path, alen, nxt = oracle.accept(toks[b], trees[b], out["argmax"][b, :n])
+        assert out["accept_len"][b] == alen and out["next_token"][b] == nxt
+        assert out["path"][b, :alen].tolist() == path.tolist()
+        assert ver.kv_len[b] == Ls[b] + alen
+        want = ref["ktree"][:, :, path]
+        got = widen_cache(k2[b, :, :, Ls[b]:Ls[b] + alen])
+        assert np.abs(got - want).max() <= TOL_F32 * np.abs(want).max()
+        assert np.all(out["argmax"][b, n:] == -1)
+    ver.close()
+
+
+def test_accept_stage_bit_exact_against_oracle():
+    """Acceptance from device argmax arrays and from logits, random trees with tiny vocabularies
+    (many matches, duplicate sibling tokens), batch of 5, sizes 1..64."""
+    cfg = wl.MODELS["tiny"]
+    w = wl.make_weights(cfg, 81, "f32")
+    ver = _verifier(cfg, w, "f32", max_nodes=64, capacity=64, max_batch=5)
+    rng = np.random.default_rng(82)
+    for trial in range(40):
+        sizes = [int(rng.integers(1, 65)) for _ in range(5)]
+        if trial == 0:
+            sizes = [1, 64, 63, 2, 33]
+        trees = [wl.random_tree(rng, n, max_children=3) for n in sizes]
+        voc = int(rng.integers(2, 6))
+        toks = [rng.integers(0, voc, n).astype(np.int32) for n in sizes]
+        am = np.full((5, 64), -1, np.int32)
+        for b, n in enumerate(sizes):
+            am[b, :n] = rng.integers(0, voc, n)
+        r = ver.accept(toks, trees, argmax_dev=torch.from_numpy(am).to(ver.device))
+        assert r["status"] == 0
+        for b, n in enumerate(sizes):
+            path, alen, nxt = oracle.accept(toks[b], trees[b], am[b, :n])
+            assert r["accept_len"][b] == alen and r["next_token"][b] == nxt
+            assert r["path"][b, :alen].tolist() == path.tolist()
+            assert np.all(r["path"][b, alen:] == -1)
+    # from logits: planted targets; ties resolved to the lowest token id
+    parents, _ = wl.make_tree("cfg5_7b_n64")
+    tokens = wl.tree_tokens(rng, parents, cfg["vocab"])
+    lg = wl.planted_logits(rng, parents, tokens, cfg["vocab"])
+    lg[3, 10] = lg[3, 500] = lg[3].max() + 1.0          # exact tie
+    full = np.zeros((5, 64, cfg["vocab"]), np.float32)
+    full[2] = lg
+    r = ver.accept([tokens[:1]] * 2 + [tokens] + [tokens[:1]] * 2,
+                   [parents[:1]] * 2 + [parents] + [parents[:1]] * 2,
+                   logits_dev=torch.from_numpy(full).to(ver.device))
+    am = lg.argmax(axis=1).astype(np.int32)
+    assert am[3] == 10
+    assert np.array_equal(r["argmax"][2].cpu().numpy(), am)
+    path, alen, nxt = oracle.accept(tokens, parents, am)
+    assert r["accept_len"][2] == alen and r["next_token"][2] == nxt
+    assert r["path"][2, :alen].tolist() == path.tolist()
+    ver.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_commit_moves_rows_in_place_without_races(dtype):
+    """Adversarial paths whose destinations are other moves' sources (0,1,3,5: slot 3 is written
+    by k=2 and read by k=3's predecessor), against a plain gather of the pre-commit cache."""
+    cfg = wl.MODELS["tiny"]
+    w = wl.make_weights(cfg, 83, dtype)
+    rng = np.random.default_rng(84)
+    ver = _verifier(cfg, w, dtype, max_nodes=64, capacity=200, max_batch=2)
+    paths = [([0, 1, 3, 5], [0]), ([0, 2, 3, 4, 5, 6, 7, 8], [0, 1, 2]), (list(range(0, 64, 2)), [0, 63]),
+             ([0] + list(range(33, 64)), list(range(64))), ([0, 1, 2, 3], [0, 5, 6])]
+    for pa, pb in paths:
+        K, V = wl.seeded_cache(cfg, int(rng.integers(1 << 30)), 200, 200, dtype, batch=2)
+        ver.set_cache(K, V, [100, 7])
+        rc = ver.commit([64, 64], [pa, pb])
+        assert rc == 0
+        assert ver.kv_len.tolist() == [100 + len(pa), 7 + len(pb)]
+        k2, v2 = ver.get_cache()
+        for b, (L, p) in enumerate(((100, pa), (7, pb))):
+            for src, got in ((K, k2), (V, v2)):
+                want = src[b].copy()
+                want[:, :, L:L + len(p)] = src[b][:, :, [L + j for j in p]]
+                # rows behind the accepted ones are scratch; everything else must be exact
+                keep = np.ones(200, bool)
+                keep[L + len(p):L + 64] = False
+                assert np.array_equal(got[b][:, :, keep], want[:, :, keep])
+    ver.close()
+
+
+def test_lossless_rounds_on_gpu_equal_greedy_decode():
+    """Verify/accept/commit rounds through the library emit exactly the oracle's greedy
+    autoregressive tokens (fp32 model, all decisions checked to be decisive)."""
+    cfg = wl.MODELS["tiny"]
+    w = wl.make_weights(cfg, 85, "f32")
+    for lw in w["layers"]:                     # sharpen the logits so that greedy choices are decisive
+        for m in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down"):
+            lw[m] = (lw[m] * np.float32(4.0)).astype(np.float32)
+    w["lm_head"] = (w["lm_head"] * np.float32(8.0)).astype(np.float32)
+    rng = np.random.default_rng(86)
+    audio = rng.standard_normal((20, cfg["d_model"])).astype(np.float32)
+    text = rng.integers(0, cfg["vocab"], 6).astype(np.int32)
+    rows = np.concatenate([audio.astype(np.float64), form_s.widen(w["tok_embed"])[text[:-1]]])
+    n_new = 24
+    ref = form_s.greedy_decode(cfg, w, rows, text[-1], n_new)
+    om, kc, vc, L, _ = oracle_prefilled(cfg, w, audio, text[:-1], 128)
+    ver = _verifier(cfg, w, "f32", max_nodes=16, capacity=128)
+    ver.set_cache(kc[None].astype(np.float32), vc[None].astype(np.float32), [L])
+    root, emitted, rounds = int(text[-1]), [], 0
+    while len(emitted) < n_new:
+        n = int(rng.integers(1, 17))
+        parents = wl.random_tree(rng, n)
+        depth, _ = oracle.tree_meta(parents)
+        tokens = rng.integers(0, cfg["vocab"], n).astype(np.int32)
+        tokens[0] = root
+        for i in range(1, n):
+            k = len(emitted) + depth[i] - 1
+            if k < len(ref) and rng.uniform() < 0.75:
+                tokens[i] = ref[k]
+        out = ver.verify_tree([tokens], [parents])
+        assert out["status"] == 0
+        alen = int(out["accept_len"][0])
+        emitted += [int(tokens[j]) for j in out["path"][0, 1:alen]] + [int(out["next_token"][0])]
+        root = int(out["next_token"][0])
+        rounds += 1
+    assert emitted[:n_new] == ref
+    assert rounds < n_new
+    assert ver.kv_len[0] == L + len(emitted)
+    ver.close()
+
+
+@pytest.mark.parametrize("dtype,tol", [("f32", TOL_F32), ("bf16", TOL_BF16)])
+def test_chain_prefill_with_audio_embeddings(dtype, tol):
+    """Audio-embedding rows enter as input embeddings of a chain tree; committing the whole chain
+    is prefill.  The resulting cache equals the oracle's prefill."""
+    cfg = wl.MODELS["tiny"]
+    w = wl.make_weights(cfg, 87, dtype)
+    rng = np.random.default_rng(88)
+    n_a, n_t = 21, 11
+    audio = rng.standard_normal((n_a, cfg["d_model"])).astype(np.float32)
+    if dtype == "bf16":
+        audio = wl.bf16_to_f32(wl.bf16_bits(audio))
+    text = rng.integers(0, cfg["vocab"], n_t).astype(np.int32)
+    om, kc, vc, L, last = oracle_prefilled(cfg, w, audio, text, 64)
+    ver = _verifier(cfg, w, dtype, max_nodes=32, capacity=64)
+    n = n_a + n_t
+    emb = torch.zeros((1, 32, cfg["d_model"]), dtype=ver.tdtype, device=ver.device)
+    emb[0, :n_a] = torch.from_numpy(audio).to(ver.device).to(ver.tdtype)
+    tok = np.zeros(n, np.int32)
+    tok[n_a:] = text
+    fw = ver.tree_forward([tok], [np.arange(-1, n - 1)], embeds=emb,
+                          use_embed=[[1] * n_a + [0] * n_t])
+    assert fw["status"] == 0
+    assert ver.commit([n], [list(range(n))]) == 0
+    assert ver.kv_len[0] == n == L
+    k1, v1 = ver.get_cache()
+    for got, want in ((k1, kc), (v1, vc)):
+        g = widen_cache(got[0, :, :, :n])
+        assert np.abs(g - want[:, :, :n]).max() <= tol * np.abs(want[:, :, :n]).max()
+    err = row_rel_err(fw["logits"][0, n - 1].cpu().numpy()[None], last[None])
+    assert err.max() <= tol
+    ver.close()
