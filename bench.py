@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-verification hot path on one MI355X.
+
+A "step" is one whole verification round through the C ABI (specasr_verify_tree): tree
+preprocessing, embedding gather, every decoder layer over the tree tokens against the resident
+KV cache, LM head + per-node argmax, greedy acceptance, in-place KV compaction, and the
+device-to-host copy of the results.  Weights, KV cache and tree live in HBM before the timed
+region starts; kv_len is reset on the host between steps.
+
+Prints ONE JSON line.  Usage: python bench.py [--gpus 1] [--steps K] [--warmup W]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(cfg, kv_len, n_nodes):
+    """Bytes one verify step must move at least: every weight once, the prefix KV once, the
+    tree's own K/V written and read once (2 bytes per element, bf16)."""
+    d, dq = cfg["d_model"], cfg["n_heads"] * cfg["head_dim"]
+    dkv, F, V, nl = cfg["n_kv_heads"] * cfg["head_dim"], cfg["d_ffn"], cfg["vocab"], cfg["n_layers"]
+    per_layer = (dq + 2 * dkv) * d + d * dq + 3 * d * F
+    weights = (nl * per_layer + V * d) * 2
+    kv_prefix = kv_len * nl * 2 * dkv * 2
+    kv_tree = 2 * n_nodes * nl * 2 * dkv * 2
+    return weights + kv_prefix + kv_tree, weights, kv_prefix
+
+
+def cpu_baseline(cfg, w_host, kc, vc, kv_len, tokens, parents, n_sample_layers):
+    """The oracle, as it stands, on the host cores: a bounded sample of the same step (the first
+    n_sample_layers decoder layers + final norm + LM head), scaled to the full layer count."""
+    import numpy as np
+    import oracle
+    sub = dict(cfg, n_layers=n_sample_layers)
+    w_sub = {k: v for k, v in w_host.items() if k != "layers"}
+    w_sub["layers"] = w_host["layers"][:n_sample_layers]
+    om = oracle.OracleModel(sub, w_sub)
+    kcs = np.ascontiguousarray(kc[0, :n_sample_layers])
+    vcs = np.ascontiguousarray(vc[0, :n_sample_layers])
+    t0 = time.perf_counter()
+    om.tree_forward(kcs, vcs, kv_len, tokens, parents, want_kv=False)
+    t_all = time.perf_counter() - t0
+    # head-only time: one more sample with a single layer, to separate layer time from LM head time
+    om1 = oracle.OracleModel(dict(cfg, n_layers=1), dict(w_sub, layers=w_host["layers"][:1]))
+    t0 = time.perf_counter()
+    om1.tree_forward(np.ascontiguousarray(kc[0, :1]), np.ascontiguousarray(vc[0, :1]), kv_len, tokens,
+                     parents, want_kv=False)
+    t_one = time.perf_counter() - t0
+    if n_sample_layers > 1:
+        t_layer = (t_all - t_one) / (n_sample_layers - 1)
+    else:
+        t_layer = t_all * 0.6
+    t_head = max(t_one - t_layer, 0.0)
+    est = t_layer * cfg["n_layers"] + t_head
+    return est, t_all + t_one, oracle.num_threads()
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg3_7b_n32")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=2)
+    ap.add_argument("--stage", default="gate_up", choices=["qkv", "o", "gate_up", "down", "lm_head"])
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU only (the verify step of one utterance on one "
+              "MI355X); --gpus N with N > 1 is not supported.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workload as wl
+    from paper_2507_18181_amd import binding as B
+    from paper_2507_18181_amd.runtime import Verifier, upload_weights
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    spec = wl.WORKLOADS[args.workload]
+    cfg = wl.MODELS[spec["model"]]
+    dtype = spec["dtype"]
+    kv_len = spec["n_audio"] + spec["n_text"]
+    parents, tokens = wl.make_tree(args.workload)
+    n = len(parents)
+    capacity = kv_len + 64
+
+    def log(msg):
+        print("[bench] " + msg, file=sys.stderr, flush=True)
+
+    log("generating %s weights on the host" % spec["model"])
+    t0 = time.perf_counter()
+    w_host = wl.make_weights(cfg, spec["seed"], dtype, threads=16)
+    t_gen = time.perf_counter() - t0
+    log("generated in %.1f s; uploading" % t_gen)
+    w_dev = upload_weights(w_host, "cuda:0")
+    log("uploaded; creating context (weight repack)")
+    keep_layers = max(args.cpu_layers, 1)
+    w_host["layers"] = w_host["layers"][:keep_layers]          # free the rest of the host copy
+    K, V = wl.seeded_cache(cfg, spec["seed"], kv_len, capacity, dtype)
+    ver = Verifier(cfg, w_dev, dtype, max_nodes=64, capacity=capacity, weights_on_device=True)
+    ver.set_cache(K, V, [kv_len])
+    assert B.specasr_uses_mfma(ver.ctx, n) == 1, "MFMA path not active"
+    torch.cuda.synchronize()
+
+    stage_id = ["qkv", "o", "gate_up", "down", "lm_head"].index(args.stage)
+
+    def step():
+        ver.kv_len[0] = kv_len
+        out = ver.verify_tree([tokens], [parents])
+        assert out["status"] == 0, out["status"]
+        return out
+
+    log("warm-up")
+    for _ in range(args.warmup):
+        out = step()
+    torch.cuda.synchronize()
+    log("timing %d steps" % args.steps)
+    assert B.specasr_profile_stage(ver.ctx, stage_id, True) == 0
+    accepted = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = step()
+        accepted += int(out["accept_len"][0])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    rc, stage_ms, stage_launches, stage_bytes = B.specasr_stage_time(ver.ctx)
+    assert rc == 0 and stage_launches > 0
+    B.specasr_profile_stage(ver.ctx, stage_id, False)
+
+    ms_per_step = dt / args.steps * 1e3
+    steps_per_s = args.steps / dt
+    total_bytes, weight_bytes, kv_bytes = algorithmic_bytes(cfg, kv_len, n)
+    step_gbs = total_bytes / (ms_per_step * 1e-3) / 1e9
+    kern_ms = stage_ms / stage_launches
+    kern_gbs = stage_bytes / (kern_ms * 1e-3) / 1e9
+
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "traffic_%s_%s.json" % (args.stage, args.workload))
+    if os.path.exists(tfile):
+        traffic = json.load(open(tfile)).get("hbm_bytes_per_launch")
+
+    result = {
+        "metric": "tree_verify_steps_per_s", "value": round(steps_per_s, 3), "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "model": spec["model"], "tree_nodes": n,
+                   "kv_prefix": kv_len, "batch": 1},
+        "verified_tokens_per_s": round(accepted / dt, 2),
+        "accept_len_mean": round(accepted / args.steps, 3),
+        "algorithmic_bytes_per_step": total_bytes,
+        "step_hbm_gbs": round(step_gbs, 1), "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4),
+        "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel (%s projection)" % args.stage,
+                     "achieved": round(kern_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(kern_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "launches_timed": stage_launches, "avg_launch_us": round(kern_ms * 1e3, 2),
+                     "bytes_per_launch": stage_bytes},
+        "weights_gen_s": round(t_gen, 1),
+    }
+    log("%.3f ms/step" % ms_per_step)
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a bounded sample")
+        kh, vh = ver.get_cache()
+        est, spent, cores = cpu_baseline(cfg, w_host, kh, vh, kv_len, tokens, parents, keep_layers)
+        result["cpu_baseline"] = {
+            "value": round(1.0 / est, 5), "unit": "steps/s", "cores": cores, "kind": "oracle",
+            "sample": "fp64 oracle timed on %d of %d decoder layers + final norm + LM head of the "
+                      "same step (%.1f s of CPU work), layer time scaled to %d layers"
+                      % (keep_layers, cfg["n_layers"], spent, cfg["n_layers"]),
+            "est_ms_per_step": round(est * 1e3, 1)}
+    print(json.dumps(result), flush=True)
+    ver.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -187,6 +187,22 @@ specasr_status specasr_commit(specasr_ctx *ctx, specasr_kv *kv, const int32_t *n
                               const int32_t *path, const int32_t *accept_len, void *workspace,
                               size_t workspace_bytes, void *stream);
 
+/* Which kernels a forward over `rows` tree nodes in total would use: 1 = the bf16 MFMA path,
+ * 0 = the dtype-generic kernels (fp32 models, SPECASR_FLAG_GENERIC_KERNELS / NO_REPACK, shapes
+ * the MFMA tiling does not cover, more than 64 rows). */
+int32_t specasr_uses_mfma(const specasr_ctx *ctx, int32_t rows);
+
+/* Measurement aid for benchmarks (no effect on results).  While enabled, every forward
+ * brackets ONE launch of the chosen projection GEMM (the layer rotates from call to call) with
+ * a pair of HIP events on the caller's stream.  specasr_stage_time waits for the recorded
+ * events and returns the accumulated kernel milliseconds and the number of launches measured
+ * since profiling was enabled, plus the weight bytes one such launch streams. */
+typedef enum { SPECASR_STAGE_QKV = 0, SPECASR_STAGE_O = 1, SPECASR_STAGE_GATE_UP = 2,
+               SPECASR_STAGE_DOWN = 3, SPECASR_STAGE_LM_HEAD = 4 } specasr_stage;
+specasr_status specasr_profile_stage(specasr_ctx *ctx, int32_t stage, int32_t enable);
+specasr_status specasr_stage_time(specasr_ctx *ctx, double *total_ms, int64_t *launches,
+                                  double *weight_bytes_per_launch);
+
 const char *specasr_strerror(specasr_status s);
 /* hipError_t value of the last failing HIP call seen by this context (0 if none). */
 int32_t specasr_last_hip_error(const specasr_ctx *ctx);

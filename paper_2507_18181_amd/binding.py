@@ -30,7 +30,9 @@ SPECASR_MAX_NODES = 64
 
 EXPORTS = ("specasr_create", "specasr_destroy", "specasr_workspace_bytes", "specasr_verify_tree",
            "specasr_tree_forward", "specasr_accept", "specasr_accept_from_logits",
-           "specasr_commit", "specasr_strerror", "specasr_last_hip_error", "specasr_abi_version")
+           "specasr_commit", "specasr_strerror", "specasr_last_hip_error", "specasr_abi_version",
+           "specasr_uses_mfma", "specasr_profile_stage", "specasr_stage_time")
+SPECASR_STAGE_QKV, SPECASR_STAGE_O, SPECASR_STAGE_GATE_UP, SPECASR_STAGE_DOWN, SPECASR_STAGE_LM_HEAD = range(5)
 
 
 class specasr_config(C.Structure):
@@ -108,6 +110,13 @@ def load_library(path=None):
     lib.specasr_last_hip_error.restype = C.c_int32
     lib.specasr_last_hip_error.argtypes = [vp]
     lib.specasr_abi_version.restype = C.c_int32
+    lib.specasr_uses_mfma.restype = C.c_int32
+    lib.specasr_uses_mfma.argtypes = [vp, C.c_int32]
+    lib.specasr_profile_stage.restype = C.c_int
+    lib.specasr_profile_stage.argtypes = [vp, C.c_int32, C.c_int32]
+    lib.specasr_stage_time.restype = C.c_int
+    lib.specasr_stage_time.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64),
+                                       C.POINTER(C.c_double)]
     if path is None:
         _lib = lib
     return lib
@@ -173,6 +182,21 @@ def specasr_destroy(ctx):
 
 def specasr_workspace_bytes(ctx, batch):
     return int(load_library().specasr_workspace_bytes(ctx, batch))
+
+
+def specasr_uses_mfma(ctx, rows):
+    return int(load_library().specasr_uses_mfma(ctx, rows))
+
+
+def specasr_profile_stage(ctx, stage, enable):
+    return load_library().specasr_profile_stage(ctx, stage, 1 if enable else 0)
+
+
+def specasr_stage_time(ctx):
+    """-> (status, total_ms, launches, weight_bytes_per_launch)."""
+    ms, n, b = C.c_double(0), C.c_int64(0), C.c_double(0)
+    rc = load_library().specasr_stage_time(ctx, C.byref(ms), C.byref(n), C.byref(b))
+    return rc, ms.value, n.value, b.value
 
 
 def specasr_last_hip_error(ctx):

@@ -11,6 +11,7 @@
 
 #include "../../include/specasr.h"
 #include "kernels.h"
+#include "kernels_mfma.h"
 
 using namespace specasr;
 
@@ -29,12 +30,31 @@ struct Staging {
 // offsets (in bytes) of the regions of a workspace sized for `rows_max` rows / `batch` sequences
 struct WsLayout {
   size_t meta, outs, rope, x, h, q, k, v, att, gu, t, logits, total;
+  size_t hb, attb, tb, part, blk_val, blk_idx;  // bf16 activations and split-k partial sums (MFMA path)
   size_t meta_words;
 };
 
 }  // namespace
 
+// Packed (MFMA-tiled) weights of one decoder layer: q|k|v and gate|up are concatenated
+// band-aligned so that each pair is one GEMM.
+struct PackedLayer {
+  PackedMatrix qkv, o, gu, down;
+};
+
 struct specasr_ctx {
+  bool fast = false;  // bf16 MFMA path available (weights repacked)
+  std::vector<PackedLayer> packed;
+  PackedMatrix lm_head;
+  std::vector<void *> owned;  // device allocations made by create
+  int col_k = 0, col_v = 0, col_up = 0;  // column offsets inside the concatenated outputs
+  size_t part_floats = 0;
+  // stage profiling (benchmark aid)
+  int prof_stage = -1;
+  std::vector<hipEvent_t> prof_ev;  // pairs
+  size_t prof_used = 0;             // events recorded and not yet accumulated
+  double prof_ms = 0.0;
+  int64_t prof_launches = 0, prof_calls = 0;  // per-row-count-independent bound of the partial-sum buffer, in floats per row
   specasr_config cfg;
   ModelDims md;
   specasr_weights w;
@@ -65,6 +85,48 @@ size_t meta_words(int rows_max, int batch) {
   return (size_t)rows_max * 10 + (size_t)batch * 3;
 }
 
+inline int pad32(int v) { return (v + 31) / 32 * 32; }
+
+// Chooses the k-split and the bands per wavefront of one skinny GEMM.  The stage is HBM bound:
+// the cost model counts bytes (weights once, partial sums written and re-read, activations
+// re-staged per workgroup from L2) and the imbalance of the last round of workgroups.
+GemmPlan plan_gemm(int n_bands, int ksteps, int nb) {
+  GemmPlan best;
+  double best_cost = 1e300;
+  const int max_chunk = kGemmMaxLds / 1024 / nb;
+  for (int chunk = 8; chunk <= max_chunk && chunk <= ((ksteps + 7) / 8) * 8; chunk += 8) {
+    const int S = (ksteps + chunk - 1) / chunk;
+    const int chunk_bal = (ksteps + S - 1) / S;  // spread the steps evenly over the S chunks
+    if ((S - 1) * chunk_bal >= ksteps) continue;
+    const size_t lds = (size_t)chunk_bal * nb * 1024;
+    int resident = (int)((160 * 1024) / (lds > 0 ? lds : 1));
+    if (resident > 8) resident = 8;
+    if (resident < 1) continue;
+    for (int bpw = 1; bpw <= 32; ++bpw) {
+      const int groups = (n_bands + 4 * bpw - 1) / (4 * bpw);
+      const long wgs = (long)groups * S;
+      const long slots = 256L * resident;
+      const long rounds = (wgs + slots - 1) / slots;
+      const double live = (double)(wgs < slots ? wgs : slots);          // workgroups running at once
+      const double per_wave_kb = (double)bpw * chunk_bal + 24.0;         // stream + start-up latency
+      const double stream = (double)rounds * per_wave_kb * live * 4.0;   // KB-equivalents
+      const double idle = live * 4.0 < 2048.0 ? 2048.0 / (live * 4.0) : 1.0;  // too few waves in flight
+      const double partial = (double)S * 32.0 * nb * n_bands * 32.0 * 4.0 / 1024.0 * 2.5;
+      const double stage = (double)wgs * chunk_bal * nb * 0.5;
+      const double cost = stream * idle + partial + stage;
+      if (cost < best_cost) {
+        best_cost = cost;
+        best.n_splits = S;
+        best.chunk_steps = chunk_bal;
+        best.bands_per_wave = bpw;
+      }
+    }
+  }
+  return best;
+}
+
+WsLayout ws_layout(const specasr_ctx *ctx, int batch);
+
 WsLayout ws_layout(const specasr_config &c, int batch) {
   WsLayout L{};
   const size_t R = (size_t)batch * c.max_nodes;
@@ -84,6 +146,27 @@ WsLayout ws_layout(const specasr_config &c, int batch) {
   L.gu = take(R * 2 * c.d_ffn * 4);
   L.t = take(R * c.d_ffn * 4);
   L.logits = take(R * c.vocab * 4);
+  L.total = off;
+  return L;
+}
+
+// Workspace of a context: the generic regions plus, when the MFMA path exists, its bf16
+// activation buffers and the split-k partial-sum buffer.
+WsLayout ws_layout(const specasr_ctx *ctx, int batch) {
+  const specasr_config &c = ctx->cfg;
+  WsLayout L = ws_layout(c, batch);
+  if (!ctx->fast) return L;
+  const size_t R = (size_t)batch * c.max_nodes;
+  const size_t dq = (size_t)c.n_heads * c.head_dim;
+  size_t off = L.total;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  L.hb = take(R * c.d_model * 2);
+  L.attb = take(R * dq * 2);
+  L.tb = take(R * c.d_ffn * 2);
+  L.part = take((R < 64 ? R : 64) * ctx->part_floats * 4);
+  const size_t nblk = (size_t)logits_argmax_blocks(c.vocab);
+  L.blk_val = take(R * nblk * 4);
+  L.blk_idx = take(R * nblk * 4);
   L.total = off;
   return L;
 }
@@ -228,7 +311,7 @@ specasr_status upload_meta(specasr_ctx *ctx, const HostStep &hs, char *ws, const
 specasr_status check_ws(const specasr_ctx *ctx, const void *ws, size_t bytes, int batch) {
   if (!ws) return SPECASR_E_WORKSPACE;
   if (((uintptr_t)ws & 255u) != 0) return SPECASR_E_WORKSPACE;
-  if (bytes < ws_layout(ctx->cfg, batch).total) return SPECASR_E_WORKSPACE;
+  if (bytes < ws_layout(ctx, batch).total) return SPECASR_E_WORKSPACE;
   return SPECASR_OK;
 }
 
@@ -267,13 +350,157 @@ void forward_generic(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, speca
   if (logits_dev) launch_scatter_logits(m, lg, ctx->cfg.max_nodes, V, logits_dev, st);
 }
 
+constexpr size_t kProfPairs = 256;
+
+// Adds the elapsed time of every recorded event pair to the totals (waits for them).
+specasr_status prof_drain(specasr_ctx *ctx) {
+  for (size_t i = 0; i + 1 < ctx->prof_used; i += 2) {
+    HIP_TRY(ctx, hipEventSynchronize(ctx->prof_ev[i + 1]));
+    float ms = 0.f;
+    HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[i], ctx->prof_ev[i + 1]));
+    ctx->prof_ms += ms;
+    ++ctx->prof_launches;
+  }
+  ctx->prof_used = 0;
+  return SPECASR_OK;
+}
+
+// Launches one projection GEMM; brackets it with events when it is the profiled one.
+void gemm_stage(specasr_ctx *ctx, int stage, bool profiled_layer, const PackedMatrix &W,
+                const uint16_t *X, int ldx, int rows, float *part, const GemmPlan &plan,
+                hipStream_t st) {
+  const bool prof = ctx->prof_stage == stage && profiled_layer && !ctx->prof_ev.empty();
+  if (prof) {
+    if (ctx->prof_used + 2 > ctx->prof_ev.size()) (void)prof_drain(ctx);
+    (void)hipEventRecord(ctx->prof_ev[ctx->prof_used], st);
+  }
+  launch_gemm_skinny(W, X, ldx, rows, part, plan, st);
+  if (prof) {
+    (void)hipEventRecord(ctx->prof_ev[ctx->prof_used + 1], st);
+    ctx->prof_used += 2;
+  }
+}
+
+// Steps 1-8 with the bf16 MFMA kernels (rows <= 64).  Residual stream, norms, softmax and all
+// accumulators stay fp32; only the MFMA operands (normalised activations, attention output,
+// SwiGLU output) are rounded to bf16.
+void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_kv *kv,
+                  const specasr_tree *tree, char *ws, const WsLayout &L, int32_t *argmax_dev,
+                  float *logits_dev, hipStream_t st) {
+  const ModelDims &md = ctx->md;
+  const int d = md.d_model, F = md.d_ffn, V = md.vocab, R = m.rows;
+  const int dq = md.n_heads * md.head_dim;
+  const int nb = R <= 32 ? 1 : 2;
+  float *x = (float *)(ws + L.x), *q = (float *)(ws + L.q), *att = (float *)(ws + L.att);
+  float *part = (float *)(ws + L.part);
+  uint16_t *hb = (uint16_t *)(ws + L.hb), *attb = (uint16_t *)(ws + L.attb), *tb = (uint16_t *)(ws + L.tb);
+  float2 *cs = (float2 *)(ws + L.rope);
+  const PackedLayer &p0 = ctx->packed[0];
+  const GemmPlan pl_qkv = plan_gemm(p0.qkv.n_bands, p0.qkv.ksteps, nb);
+  const GemmPlan pl_o = plan_gemm(p0.o.n_bands, p0.o.ksteps, nb);
+  const GemmPlan pl_gu = plan_gemm(p0.gu.n_bands, p0.gu.ksteps, nb);
+  const GemmPlan pl_dn = plan_gemm(p0.down.n_bands, p0.down.ksteps, nb);
+  const GemmPlan pl_lm = plan_gemm(ctx->lm_head.n_bands, ctx->lm_head.ksteps, nb);
+
+  if (getenv("SPECASR_DEBUG")) {
+    const GemmPlan *pls[5] = {&pl_qkv, &pl_o, &pl_gu, &pl_dn, &pl_lm};
+    const char *nm[5] = {"qkv", "o", "gate_up", "down", "lm_head"};
+    const PackedMatrix *pm[5] = {&p0.qkv, &p0.o, &p0.gu, &p0.down, &ctx->lm_head};
+    for (int i = 0; i < 5; ++i)
+      fprintf(stderr, "[specasr] %-8s bands=%d ksteps=%d rows=%d: splits=%d chunk=%d bands/wave=%d\n", nm[i],
+              pm[i]->n_bands, pm[i]->ksteps, R, pls[i]->n_splits, pls[i]->chunk_steps, pls[i]->bands_per_wave);
+  }
+  launch_rope_table(m, md.head_dim, md.rope_theta, cs, st);
+  launch_embed(m, 1, ctx->w.tok_embed, tree->input_embeds, ctx->cfg.max_nodes, d, x, st);
+  int pending = 0, pending_ld = 0;  // partial sums of the previous down projection, not yet added to x
+  const int prof_layer = (int)(ctx->prof_calls++ % md.n_layers);
+  for (int l = 0; l < md.n_layers; ++l) {
+    const bool pl = l == prof_layer;
+    const specasr_layer_weights &lw = ctx->layers[l];
+    const PackedLayer &pk = ctx->packed[l];
+    launch_residual_norm(x, part, pending, R, pending_ld, lw.attn_norm, d, md.rms_eps, hb, st);
+    gemm_stage(ctx, SPECASR_STAGE_QKV, pl, pk.qkv, hb, d, R, part, pl_qkv, st);
+    launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, ctx->col_k, ctx->col_v, cs, q, kv->k, kv->v, st);
+    launch_attention_generic(m, md, g, l, q, kv->k, kv->v, att, st);
+    launch_to_bf16(att, (int64_t)R * dq, attb, st);
+    gemm_stage(ctx, SPECASR_STAGE_O, pl, pk.o, attb, dq, R, part, pl_o, st);
+    launch_residual_norm(x, part, pl_o.n_splits, R, pk.o.ldo, lw.ffn_norm, d, md.rms_eps, hb, st);
+    gemm_stage(ctx, SPECASR_STAGE_GATE_UP, pl, pk.gu, hb, d, R, part, pl_gu, st);
+    launch_swiglu_finish(part, pl_gu.n_splits, R, pk.gu.ldo, ctx->col_up, F, tb, st);
+    gemm_stage(ctx, SPECASR_STAGE_DOWN, pl, pk.down, tb, F, R, part, pl_dn, st);
+    pending = pl_dn.n_splits;
+    pending_ld = pk.down.ldo;
+  }
+  launch_residual_norm(x, part, pending, R, pending_ld, ctx->w.final_norm, d, md.rms_eps, hb, st);
+  gemm_stage(ctx, SPECASR_STAGE_LM_HEAD, true, ctx->lm_head, hb, d, R, part, pl_lm, st);
+  launch_logits_argmax(m, part, pl_lm.n_splits, ctx->lm_head.ldo, V, ctx->cfg.max_nodes, logits_dev,
+                       (float *)(ws + L.blk_val), (int *)(ws + L.blk_idx), argmax_dev, st);
+}
+
 specasr_status forward_common(specasr_ctx *ctx, specasr_kv *kv, const specasr_tree *tree,
                               int32_t *argmax_dev, float *logits_dev, char *ws,
                               const WsLayout &L, const HostStep &hs, hipStream_t st) {
   KvGeom g{kv->capacity, ctx->md.n_layers, ctx->md.n_kv_heads, ctx->md.head_dim};
   StepMeta m = device_meta(ctx, ws, L, hs.batch, hs);
-  forward_generic(ctx, m, g, kv, tree, ws, L, argmax_dev, logits_dev, st);
+  if (ctx->fast && m.rows <= 64)
+    forward_fast(ctx, m, g, kv, tree, ws, L, argmax_dev, logits_dev, st);
+  else
+    forward_generic(ctx, m, g, kv, tree, ws, L, argmax_dev, logits_dev, st);
   HIP_TRY(ctx, hipGetLastError());
+  return SPECASR_OK;
+}
+
+// One-time repack of the bf16 weights into MFMA-tile order (values unchanged).  Allocates the
+// packed copies; q|k|v and gate|up are concatenated, each part starting on a 32-row band.
+specasr_status build_packed(specasr_ctx *ctx) {
+  const specasr_config &c = ctx->cfg;
+  const int d = c.d_model, F = c.d_ffn, dq = c.n_heads * c.head_dim, dkv = c.n_kv_heads * c.head_dim;
+  HIP_TRY(ctx, gemm_skinny_set_lds_limit());
+  auto alloc = [&](PackedMatrix &pm, int n_out_padded, int K) -> hipError_t {
+    pm.n_bands = n_out_padded / 32;
+    pm.ksteps = K / 16;
+    pm.ldo = n_out_padded;
+    hipError_t e = hipMalloc(&pm.data, (size_t)n_out_padded * K * 2);
+    if (e == hipSuccess) ctx->owned.push_back(pm.data);
+    return e;
+  };
+  ctx->col_k = pad32(dq);
+  ctx->col_v = ctx->col_k + pad32(dkv);
+  ctx->col_up = pad32(F);
+  ctx->packed.resize(c.n_layers);
+  hipStream_t st = nullptr;
+  for (int l = 0; l < c.n_layers; ++l) {
+    const specasr_layer_weights &lw = ctx->layers[l];
+    PackedLayer &pk = ctx->packed[l];
+    HIP_TRY(ctx, alloc(pk.qkv, ctx->col_v + pad32(dkv), d));
+    launch_repack(lw.wq, dq, d, pk.qkv.data, 0, st);
+    launch_repack(lw.wk, dkv, d, pk.qkv.data, ctx->col_k / 32, st);
+    launch_repack(lw.wv, dkv, d, pk.qkv.data, ctx->col_v / 32, st);
+    HIP_TRY(ctx, alloc(pk.o, pad32(d), dq));
+    launch_repack(lw.wo, d, dq, pk.o.data, 0, st);
+    HIP_TRY(ctx, alloc(pk.gu, 2 * pad32(F), d));
+    launch_repack(lw.w_gate, F, d, pk.gu.data, 0, st);
+    launch_repack(lw.w_up, F, d, pk.gu.data, ctx->col_up / 32, st);
+    HIP_TRY(ctx, alloc(pk.down, pad32(d), F));
+    launch_repack(lw.w_down, d, F, pk.down.data, 0, st);
+    HIP_TRY(ctx, hipGetLastError());
+  }
+  HIP_TRY(ctx, alloc(ctx->lm_head, pad32(c.vocab), d));
+  launch_repack(ctx->w.lm_head, c.vocab, d, ctx->lm_head.data, 0, st);
+  HIP_TRY(ctx, hipGetLastError());
+  HIP_TRY(ctx, hipStreamSynchronize(st));
+  // bound of the partial-sum buffer: floats per activation row, over every GEMM and both widths
+  size_t bound = 0;
+  const PackedLayer &p0 = ctx->packed[0];
+  const PackedMatrix *mats[5] = {&p0.qkv, &p0.o, &p0.gu, &p0.down, &ctx->lm_head};
+  for (const PackedMatrix *pm : mats)
+    for (int nb = 1; nb <= 2; ++nb) {
+      const GemmPlan pl = plan_gemm(pm->n_bands, pm->ksteps, nb);
+      const size_t need = (size_t)pl.n_splits * pm->ldo;
+      if (need > bound) bound = need;
+    }
+  ctx->part_floats = bound;
+  ctx->fast = true;
   return SPECASR_OK;
 }
 
@@ -306,6 +533,45 @@ const char *specasr_strerror(specasr_status s) {
 
 int32_t specasr_last_hip_error(const specasr_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
 
+int32_t specasr_uses_mfma(const specasr_ctx *ctx, int32_t rows) {
+  return (ctx && ctx->fast && rows >= 1 && rows <= 64) ? 1 : 0;
+}
+
+specasr_status specasr_profile_stage(specasr_ctx *ctx, int32_t stage, int32_t enable) {
+  if (!ctx) return SPECASR_E_NULL;
+  if (stage < SPECASR_STAGE_QKV || stage > SPECASR_STAGE_LM_HEAD) return SPECASR_E_UNSUPPORTED;
+  if (!ctx->fast) return SPECASR_E_UNSUPPORTED;
+  if (enable) {
+    while (ctx->prof_ev.size() < 2 * kProfPairs) {
+      hipEvent_t e;
+      HIP_TRY(ctx, hipEventCreate(&e));
+      ctx->prof_ev.push_back(e);
+    }
+    ctx->prof_stage = stage;
+    ctx->prof_used = 0;
+    ctx->prof_ms = 0.0;
+    ctx->prof_launches = 0;
+  } else {
+    ctx->prof_stage = -1;
+  }
+  return SPECASR_OK;
+}
+
+specasr_status specasr_stage_time(specasr_ctx *ctx, double *total_ms, int64_t *launches,
+                                  double *weight_bytes_per_launch) {
+  if (!ctx || !total_ms || !launches || !weight_bytes_per_launch) return SPECASR_E_NULL;
+  if (ctx->prof_stage < 0 || !ctx->fast) return SPECASR_E_UNSUPPORTED;
+  specasr_status s = prof_drain(ctx);
+  if (s != SPECASR_OK) return s;
+  const specasr_config &c = ctx->cfg;
+  const double d = c.d_model, dq = (double)c.n_heads * c.head_dim, dkv = (double)c.n_kv_heads * c.head_dim;
+  const double elems[5] = {(dq + 2 * dkv) * d, d * dq, 2.0 * c.d_ffn * d, d * c.d_ffn, (double)c.vocab * d};
+  *total_ms = ctx->prof_ms;
+  *launches = ctx->prof_launches;
+  *weight_bytes_per_launch = elems[ctx->prof_stage] * 2.0;
+  return SPECASR_OK;
+}
+
 specasr_status specasr_create(const specasr_config *cfg, const specasr_weights *weights,
                               specasr_ctx **out) {
   if (!cfg || !weights || !out) return SPECASR_E_NULL;
@@ -336,6 +602,18 @@ specasr_status specasr_create(const specasr_config *cfg, const specasr_weights *
   ctx->layers.assign(weights->layers, weights->layers + c.n_layers);
   ctx->w = *weights;
   ctx->w.layers = ctx->layers.data();
+  const bool want_fast = c.dtype == SPECASR_BF16 && !(c.flags & SPECASR_FLAG_GENERIC_KERNELS) &&
+                         !(c.flags & SPECASR_FLAG_NO_REPACK) && c.d_model % 16 == 0 &&
+                         c.d_ffn % 16 == 0 && (c.n_heads * c.head_dim) % 16 == 0;
+  if (want_fast) {
+    specasr_status rs = build_packed(ctx);
+    if (rs != SPECASR_OK) {
+      const int32_t he = ctx->last_hip;
+      specasr_destroy(ctx);
+      (void)he;
+      return rs;
+    }
+  }
   *out = ctx;
   return SPECASR_OK;
 }
@@ -347,12 +625,14 @@ void specasr_destroy(specasr_ctx *ctx) {
     if (ctx->stage[i].done) (void)hipEventDestroy(ctx->stage[i].done);
   }
   if (ctx->out_host) (void)hipHostFree(ctx->out_host);
+  for (void *p : ctx->owned) (void)hipFree(p);
+  for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
   delete ctx;
 }
 
 size_t specasr_workspace_bytes(const specasr_ctx *ctx, int32_t batch) {
   if (!ctx || batch < 1 || batch > ctx->cfg.max_batch) return 0;
-  return ws_layout(ctx->cfg, batch).total;
+  return ws_layout(ctx, batch).total;
 }
 
 specasr_status specasr_tree_forward(specasr_ctx *ctx, specasr_kv *kv, const specasr_tree *tree,
@@ -367,7 +647,7 @@ specasr_status specasr_tree_forward(specasr_ctx *ctx, specasr_kv *kv, const spec
   if (s != SPECASR_OK) return s;
   hipStream_t st = (hipStream_t)stream;
   char *ws = (char *)workspace;
-  const WsLayout L = ws_layout(ctx->cfg, kv->batch);
+  const WsLayout L = ws_layout(ctx, kv->batch);
   HostStep hs;
   build_step(ctx, tree, kv->batch, kv->kv_len, &hs);
   s = upload_meta(ctx, hs, ws, L, st);
@@ -386,7 +666,7 @@ specasr_status specasr_accept(specasr_ctx *ctx, const specasr_tree *tree, int32_
   if (s != SPECASR_OK) return s;
   hipStream_t st = (hipStream_t)stream;
   char *ws = (char *)workspace;
-  const WsLayout L = ws_layout(ctx->cfg, batch);
+  const WsLayout L = ws_layout(ctx, batch);
   HostStep hs;
   build_step(ctx, tree, batch, nullptr, &hs);
   s = upload_meta(ctx, hs, ws, L, st);
@@ -410,7 +690,7 @@ specasr_status specasr_accept_from_logits(specasr_ctx *ctx, const specasr_tree *
   if (s != SPECASR_OK) return s;
   hipStream_t st = (hipStream_t)stream;
   char *ws = (char *)workspace;
-  const WsLayout L = ws_layout(ctx->cfg, batch);
+  const WsLayout L = ws_layout(ctx, batch);
   HostStep hs;
   build_step(ctx, tree, batch, nullptr, &hs);
   s = upload_meta(ctx, hs, ws, L, st);
@@ -445,7 +725,7 @@ specasr_status specasr_commit(specasr_ctx *ctx, specasr_kv *kv, const int32_t *n
   if (s != SPECASR_OK) return s;
   hipStream_t st = (hipStream_t)stream;
   char *ws = (char *)workspace;
-  const WsLayout L = ws_layout(c, B);
+  const WsLayout L = ws_layout(ctx, B);
   // stage [kv_len | accept_len | path] in the metadata region
   Staging *sgp = nullptr;
   s = next_slot(ctx, &sgp);
@@ -485,7 +765,7 @@ specasr_status specasr_verify_tree(specasr_ctx *ctx, specasr_kv *kv, const speca
   const int B = kv->batch;
   hipStream_t st = (hipStream_t)stream;
   char *ws = (char *)workspace;
-  const WsLayout L = ws_layout(c, B);
+  const WsLayout L = ws_layout(ctx, B);
   HostStep hs;
   build_step(ctx, tree, B, kv->kv_len, &hs);
   s = upload_meta(ctx, hs, ws, L, st);

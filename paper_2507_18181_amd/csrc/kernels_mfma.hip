@@ -1,0 +1,349 @@
+// bf16 MFMA stages of the tree-verification path for gfx950 (CDNA4, wave64).
+//
+// The projections of the decoder are skinny GEMMs: at most 64 tree-node rows against every
+// weight of the model, so each weight byte is used once per call and the stage is bound by HBM
+// bandwidth.  Design:
+//   * Weights are repacked once (specasr_create) into MFMA-operand order: the matrix is cut into
+//     tiles of 32 output features x 16 input features; one tile is 1 KB laid out exactly as the A
+//     operand of v_mfma_f32_32x32x16_bf16 (lane l holds row l%32, k = 8*(l/32)..+7), and the tiles
+//     of one 32-row band are contiguous along k.  A wavefront therefore streams its band with
+//     one fully coalesced 16-byte load per lane per tile and feeds it to the matrix core with no
+//     shuffle and no LDS round trip.
+//   * The activations (the B operand, <= 64 rows) are tiny: the workgroup stages its k-chunk of
+//     them into LDS once, already in B-operand order, and every wavefront re-reads them from there.
+//   * Work is split over (k-chunk, band group) so that a few thousand wavefronts each stream a
+//     contiguous span with a ring of loads in flight; partial sums over the k-chunks are written
+//     to a small fp32 buffer and reduced, in a fixed order, by the consumer stage.
+#include "kernels.h"
+#include "kernels_mfma.h"
+
+namespace specasr {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+__device__ __forceinline__ u32x4 load_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }
+
+// --------------------------------------------------------------------------- weight repack
+// dst tile (band, kt), lane l, element i  <-  src[band*32 + l%32][kt*16 + 8*(l/32) + i]
+// Rows >= n_out (padding of the last band) are zero.  `row0` is the first packed row written,
+// so several source matrices can be concatenated band-aligned into one packed matrix.
+__global__ void repack_kernel(const uint16_t *src, int n_out, int K, uint16_t *dst, int band0) {
+  const int ksteps = K / 16;
+  const int64_t tile = blockIdx.x;  // over (n_out padded / 32) * ksteps
+  const int band = (int)(tile / ksteps), kt = (int)(tile - (int64_t)band * ksteps);
+  const int l = threadIdx.x;  // 64 lanes
+  const int row = band * 32 + (l & 31);
+  u32x4 v = (u32x4){0u, 0u, 0u, 0u};
+  if (row < n_out) v = *reinterpret_cast<const u32x4 *>(src + (int64_t)row * K + kt * 16 + 8 * (l >> 5));
+  reinterpret_cast<u32x4 *>(dst)[((int64_t)(band0 + band) * ksteps + kt) * 64 + l] = v;
+}
+
+void launch_repack(const void *src, int n_out, int K, void *dst, int band0, hipStream_t st) {
+  const int bands = (n_out + 31) / 32;
+  const int64_t tiles = (int64_t)bands * (K / 16);
+  repack_kernel<<<(unsigned)tiles, 64, 0, st>>>((const uint16_t *)src, n_out, K, (uint16_t *)dst, band0);
+}
+
+// --------------------------------------------------------------------------- skinny GEMM
+// part[s][row][o] = sum over k in chunk s of X[row][k] * W[o][k]
+// grid.x = n_splits * n_groups; block = 256 (4 wavefronts); wavefront w of group g owns bands
+// [(g*4+w)*bpw, +bpw).  LDS: X chunk in B-operand order, [kstep][NB][64 lanes] x 16 bytes.
+template <int NB, int U>
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4 *__restrict__ Wp,
+                                                          const uint16_t *__restrict__ X, int ldx,
+                                                          float *__restrict__ part, int ldo,
+                                                          int rows, int n_bands, int ksteps_all,
+                                                          int n_splits, int chunk_steps, int bpw) {
+  extern __shared__ u32x4 lds[];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int s = blockIdx.x % n_splits, grp = blockIdx.x / n_splits;
+  const int ks0 = s * chunk_steps;
+  const int nks = min(chunk_steps, ksteps_all - ks0);  // k-steps of this chunk
+  const int b0 = min((grp * 4 + wave) * bpw, n_bands), b1 = min(b0 + bpw, n_bands);
+  const int nblk = (b1 - b0) * nks;
+
+  // start the weight stream before anything else
+  u32x4 buf[U];
+  int pf_band = b0, pf_k = 0, issued = 0;  // next tile to prefetch
+  auto tile_ptr = [&](int band, int k) { return Wp + ((int64_t)band * ksteps_all + ks0 + k) * 64 + lane; };
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    buf[u] = (u32x4){0u, 0u, 0u, 0u};
+    if (issued < nblk) {
+      buf[u] = load_stream(tile_ptr(pf_band, pf_k));
+      ++issued;
+      if (++pf_k == nks) { pf_k = 0; ++pf_band; }
+    }
+  }
+  // stage the activation chunk: slot (kstep, nb, l) <- X[nb*32 + l%32][16*(ks0+kstep) + 8*(l/32) ..+7]
+  for (int idx = threadIdx.x; idx < nks * NB * 64; idx += 256) {
+    const int l = idx & 63, blk = idx >> 6;
+    const int nb = blk % NB, kstep = blk / NB;
+    const int r = nb * 32 + (l & 31);
+    u32x4 v = (u32x4){0u, 0u, 0u, 0u};
+    if (r < rows) v = *reinterpret_cast<const u32x4 *>(X + (int64_t)r * ldx + 16 * (ks0 + kstep) + 8 * (l >> 5));
+    lds[idx] = v;
+  }
+  __syncthreads();
+
+  f32x16 acc[NB];
+#pragma unroll
+  for (int n = 0; n < NB; ++n)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[n][j] = 0.f;
+  int k = 0, band = b0;
+  for (int done = 0; done < nblk; done += U) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (done + u < nblk) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, buf[u]);
+        if (issued < nblk) {
+          buf[u] = load_stream(tile_ptr(pf_band, pf_k));
+          ++issued;
+          if (++pf_k == nks) { pf_k = 0; ++pf_band; }
+        }
+#pragma unroll
+        for (int n = 0; n < NB; ++n) {
+          const bf16x8 b = __builtin_bit_cast(bf16x8, lds[(k * NB + n) * 64 + lane]);
+          acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[n], 0, 0, 0);
+        }
+        if (++k == nks) {
+          // C layout: lane l holds node column l%32 and output rows 8*(j/4) + 4*(l/32) + j%4
+#pragma unroll
+          for (int n = 0; n < NB; ++n) {
+            const int r = n * 32 + (lane & 31);
+            if (r < rows) {
+              float *dst = part + ((int64_t)s * rows + r) * ldo + band * 32 + 4 * (lane >> 5);
+#pragma unroll
+              for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<float4 *>(dst + 8 * q) =
+                    make_float4(acc[n][4 * q], acc[n][4 * q + 1], acc[n][4 * q + 2], acc[n][4 * q + 3]);
+            }
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[n][j] = 0.f;
+          }
+          k = 0;
+          ++band;
+        }
+      }
+    }
+  }
+}
+
+void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *X, int ldx, int rows, float *part,
+                        const GemmPlan &plan, hipStream_t st) {
+  const int groups = (W.n_bands + 4 * plan.bands_per_wave - 1) / (4 * plan.bands_per_wave);
+  const dim3 grid(groups * plan.n_splits);
+  const int nb = rows <= 32 ? 1 : 2;
+  const size_t lds = (size_t)plan.chunk_steps * nb * 64 * 16;
+  if (nb == 1)
+    gemm_skinny_kernel<1, 8><<<grid, 256, lds, st>>>((const u32x4 *)W.data, X, ldx, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits, plan.chunk_steps, plan.bands_per_wave);
+  else
+    gemm_skinny_kernel<2, 8><<<grid, 256, lds, st>>>((const u32x4 *)W.data, X, ldx, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits, plan.chunk_steps, plan.bands_per_wave);
+}
+
+hipError_t gemm_skinny_set_lds_limit() {
+  hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<1, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmMaxLds);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute((const void *)gemm_skinny_kernel<2, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmMaxLds);
+}
+
+// --------------------------------------------------------------------------- consumers of partial sums
+// x[r][:] += sum_s part[s][r][:]   (n_splits may be 0: plain norm)
+// hb[r][:]  = bf16( x[r][:] * rsqrt(mean(x^2) + eps) * gain )
+__global__ __launch_bounds__(256) void residual_norm_kernel(float *x, const float *part, int n_splits,
+                                                            int rows, int ldp, const uint16_t *gain,
+                                                            int d, float eps, uint16_t *hb) {
+  __shared__ float red[16];
+  const int r = blockIdx.x;
+  float *xr = x + (int64_t)r * d;
+  float ss = 0.f;
+  for (int c = threadIdx.x * 4; c < d; c += 1024) {
+    float4 v = *reinterpret_cast<const float4 *>(xr + c);
+    for (int s = 0; s < n_splits; ++s) {
+      const float4 p = *reinterpret_cast<const float4 *>(part + ((int64_t)s * rows + r) * ldp + c);
+      v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    }
+    if (n_splits > 0) *reinterpret_cast<float4 *>(xr + c) = v;
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = block_sum(ss, red);
+  const float rs = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int c = threadIdx.x * 4; c < d; c += 1024) {
+    const float4 v = *reinterpret_cast<const float4 *>(xr + c);
+    const uint2 g = *reinterpret_cast<const uint2 *>(gain + c);
+    uint2 o;
+    o.x = (uint32_t)f32_to_bf16_bits(v.x * rs * bf16_bits_to_f32(g.x & 0xffffu)) |
+          ((uint32_t)f32_to_bf16_bits(v.y * rs * bf16_bits_to_f32(g.x >> 16)) << 16);
+    o.y = (uint32_t)f32_to_bf16_bits(v.z * rs * bf16_bits_to_f32(g.y & 0xffffu)) |
+          ((uint32_t)f32_to_bf16_bits(v.w * rs * bf16_bits_to_f32(g.y >> 16)) << 16);
+    *reinterpret_cast<uint2 *>(hb + (int64_t)r * d + c) = o;
+  }
+}
+
+void launch_residual_norm(float *x, const float *part, int n_splits, int rows, int ldp,
+                          const void *gain, int d, float eps, uint16_t *hb, hipStream_t st) {
+  residual_norm_kernel<<<rows, 256, 0, st>>>(x, part, n_splits, rows, ldp, (const uint16_t *)gain, d, eps, hb);
+}
+
+// q, k, v = sum of partials; rotary embedding at the node's depth position (Sec. II-B: each
+// branch is verified as its own sequence, so position = kv_len + depth); q -> fp32 [rows][H*hd],
+// k, v -> bf16 cache slot kv_len + node.  Packed output columns: [q | pad | k | pad | v].
+__global__ __launch_bounds__(256) void qkv_finish_kernel(StepMeta m, KvGeom g, int layer, int H, int Hkv,
+                                                         int hd, const float *part, int n_splits,
+                                                         int ldp, int col_k, int col_v,
+                                                         const float2 *cs, float *q, uint16_t *kc,
+                                                         uint16_t *vc) {
+  const int r = blockIdx.x, half = hd / 2, rows = m.rows;
+  const float2 *csr = cs + (int64_t)r * half;
+  const int seq = m.seq[r];
+  const int64_t slot = m.slot[r];
+  auto val = [&](int col) {
+    float v = 0.f;
+    for (int s = 0; s < n_splits; ++s) v += part[((int64_t)s * rows + r) * ldp + col];
+    return v;
+  };
+  for (int idx = threadIdx.x; idx < (H + Hkv) * half; idx += 256) {
+    const int a = idx / half, j = idx - a * half;
+    const float2 c = csr[j];
+    if (a < H) {
+      const float x0 = val(a * hd + j), x1 = val(a * hd + j + half);
+      q[((int64_t)r * H + a) * hd + j] = x0 * c.x - x1 * c.y;
+      q[((int64_t)r * H + a) * hd + j + half] = x1 * c.x + x0 * c.y;
+    } else {
+      const int b = a - H;
+      const float x0 = val(col_k + b * hd + j), x1 = val(col_k + b * hd + j + half);
+      const int64_t base = g.row(seq, layer, b, slot);
+      kc[base + j] = f32_to_bf16_bits(x0 * c.x - x1 * c.y);
+      kc[base + j + half] = f32_to_bf16_bits(x1 * c.x + x0 * c.y);
+      vc[base + j] = f32_to_bf16_bits(val(col_v + b * hd + j));
+      vc[base + j + half] = f32_to_bf16_bits(val(col_v + b * hd + j + half));
+    }
+  }
+}
+
+void launch_qkv_finish(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
+                       const float *part, int n_splits, int ldp, int col_k, int col_v,
+                       const float2 *cs, float *q, void *kc, void *vc, hipStream_t st) {
+  qkv_finish_kernel<<<m.rows, 256, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, md.head_dim, part, n_splits, ldp, col_k, col_v, cs, q, (uint16_t *)kc, (uint16_t *)vc);
+}
+
+// t[r][f] = bf16( silu(sum_s gate) * (sum_s up) ); gate at column f, up at column col_up + f
+__global__ __launch_bounds__(256) void swiglu_finish_kernel(const float *part, int n_splits, int rows,
+                                                            int ldp, int col_up, int F, uint16_t *t) {
+  const int r = blockIdx.y;
+  const int f = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (f >= F) return;
+  float4 gt = make_float4(0.f, 0.f, 0.f, 0.f), up = gt;
+  for (int s = 0; s < n_splits; ++s) {
+    const float *p = part + ((int64_t)s * rows + r) * ldp;
+    const float4 a = *reinterpret_cast<const float4 *>(p + f);
+    const float4 b = *reinterpret_cast<const float4 *>(p + col_up + f);
+    gt.x += a.x; gt.y += a.y; gt.z += a.z; gt.w += a.w;
+    up.x += b.x; up.y += b.y; up.z += b.z; up.w += b.w;
+  }
+  auto act = [](float gv, float uv) { return gv / (1.0f + __expf(-gv)) * uv; };
+  uint2 o;
+  o.x = (uint32_t)f32_to_bf16_bits(act(gt.x, up.x)) | ((uint32_t)f32_to_bf16_bits(act(gt.y, up.y)) << 16);
+  o.y = (uint32_t)f32_to_bf16_bits(act(gt.z, up.z)) | ((uint32_t)f32_to_bf16_bits(act(gt.w, up.w)) << 16);
+  *reinterpret_cast<uint2 *>(t + (int64_t)r * F + f) = o;
+}
+
+void launch_swiglu_finish(const float *part, int n_splits, int rows, int ldp, int col_up, int F,
+                          uint16_t *t, hipStream_t st) {
+  dim3 grid((F / 4 + 255) / 256, rows);
+  swiglu_finish_kernel<<<grid, 256, 0, st>>>(part, n_splits, rows, ldp, col_up, F, t);
+}
+
+// fp32 -> bf16 row conversion (attention output feeding the output projection)
+__global__ void to_bf16_kernel(const float *src, int64_t n, uint16_t *dst) {
+  int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i >= n) return;
+  const float4 v = *reinterpret_cast<const float4 *>(src + i);
+  uint2 o;
+  o.x = (uint32_t)f32_to_bf16_bits(v.x) | ((uint32_t)f32_to_bf16_bits(v.y) << 16);
+  o.y = (uint32_t)f32_to_bf16_bits(v.z) | ((uint32_t)f32_to_bf16_bits(v.w) << 16);
+  *reinterpret_cast<uint2 *>(dst + i) = o;
+}
+
+void launch_to_bf16(const float *src, int64_t n, uint16_t *dst, hipStream_t st) {
+  to_bf16_kernel<<<(unsigned)((n / 4 + 255) / 256), 256, 0, st>>>(src, n, dst);
+}
+
+// logits[r][v] = sum_s part[s][r][v]; per-(row, block) best (value, lowest index); optional
+// store of the logits into the caller's padded array.  A second tiny kernel merges the blocks.
+__global__ __launch_bounds__(256) void logits_argmax_kernel(StepMeta m, const float *part, int n_splits,
+                                                            int ldp, int V, int max_nodes,
+                                                            float *logits_out, float *blk_val,
+                                                            int *blk_idx) {
+  __shared__ float bv[4];
+  __shared__ int bi[4];
+  const int r = blockIdx.y, rows = m.rows;
+  const int v0 = (blockIdx.x * 256 + threadIdx.x) * 4;
+  float best = -INFINITY;
+  int besti = 0x7fffffff;
+  if (v0 < V) {
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = 0; s < n_splits; ++s) {
+      const float4 p = *reinterpret_cast<const float4 *>(part + ((int64_t)s * rows + r) * ldp + v0);
+      a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
+    }
+    const float vals[4] = {a.x, a.y, a.z, a.w};
+    if (logits_out) {
+      float *dst = logits_out + ((int64_t)m.seq[r] * max_nodes + m.node[r]) * V + v0;
+      for (int i = 0; i < 4; ++i)
+        if (v0 + i < V) dst[i] = vals[i];
+    }
+    for (int i = 0; i < 4; ++i)
+      if (v0 + i < V && vals[i] > best) { best = vals[i]; besti = v0 + i; }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(best, o, 64);
+    const int oi = __shfl_xor(besti, o, 64);
+    if (ov > best || (ov == best && oi < besti)) { best = ov; besti = oi; }
+  }
+  if ((threadIdx.x & 63) == 0) { bv[threadIdx.x >> 6] = best; bi[threadIdx.x >> 6] = besti; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w)
+      if (bv[w] > best || (bv[w] == best && bi[w] < besti)) { best = bv[w]; besti = bi[w]; }
+    blk_val[(int64_t)r * gridDim.x + blockIdx.x] = best;
+    blk_idx[(int64_t)r * gridDim.x + blockIdx.x] = besti;
+  }
+}
+
+__global__ __launch_bounds__(64) void argmax_merge_kernel(StepMeta m, const float *blk_val,
+                                                          const int *blk_idx, int n_blk,
+                                                          int max_nodes, int32_t *argmax) {
+  const int r = blockIdx.x;
+  float best = -INFINITY;
+  int besti = 0x7fffffff;
+  for (int b = threadIdx.x; b < n_blk; b += 64) {
+    const float v = blk_val[(int64_t)r * n_blk + b];
+    const int i = blk_idx[(int64_t)r * n_blk + b];
+    if (v > best || (v == best && i < besti)) { best = v; besti = i; }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(best, o, 64);
+    const int oi = __shfl_xor(besti, o, 64);
+    if (ov > best || (ov == best && oi < besti)) { best = ov; besti = oi; }
+  }
+  if (threadIdx.x == 0) argmax[m.seq[r] * max_nodes + m.node[r]] = besti == 0x7fffffff ? 0 : besti;
+}
+
+int logits_argmax_blocks(int V) { return ((V + 3) / 4 + 255) / 256; }
+
+void launch_logits_argmax(const StepMeta &m, const float *part, int n_splits, int ldp, int V,
+                          int max_nodes, float *logits_out, float *blk_val, int *blk_idx,
+                          int32_t *argmax, hipStream_t st) {
+  const int n_blk = logits_argmax_blocks(V);
+  dim3 grid(n_blk, m.rows);
+  logits_argmax_kernel<<<grid, 256, 0, st>>>(m, part, n_splits, ldp, V, max_nodes, logits_out, blk_val, blk_idx);
+  argmax_merge_kernel<<<m.rows, 64, 0, st>>>(m, blk_val, blk_idx, n_blk, max_nodes, argmax);
+}
+
+}  // namespace specasr

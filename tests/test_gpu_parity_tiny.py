@@ -40,6 +40,8 @@ def test_cfg1_forward_and_round(dtype, flags, tol):
     cfg, w, audio, text, parents, tokens = _cfg1(dtype)
     om, kc, vc, L, _ = oracle_prefilled(cfg, w, audio, text, 96)
     ver = _verifier(cfg, w, dtype, max_nodes=8, capacity=96, flags=flags)
+    from paper_2507_18181_amd import binding as B
+    assert B.specasr_uses_mfma(ver.ctx, 8) == (1 if (dtype == "bf16" and flags == 0) else 0)
     ver.set_cache(_store_cache(kc, dtype), _store_cache(vc, dtype), [L])
     k0, v0 = ver.get_cache()
     ref = om.tree_forward(k0[0], v0[0], L, tokens, parents)       # oracle reads the GPU's cache bits
