@@ -31,6 +31,7 @@ struct Staging {
 struct WsLayout {
   size_t meta, outs, rope, x, h, q, k, v, att, gu, t, logits, total;
   size_t hb, attb, tb, part, blk_val, blk_idx;  // bf16 activations and split-k partial sums (MFMA path)
+  size_t qb, attn_o, attn_ml;                   // MFMA attention: bf16 queries, per-chunk partial outputs
   size_t meta_words;
 };
 
@@ -94,9 +95,11 @@ GemmPlan plan_gemm(int n_bands, int ksteps, int nb) {
   GemmPlan best;
   double best_cost = 1e300;
   const int max_chunk = kGemmMaxLds / 1024 / nb;
-  for (int chunk = 8; chunk <= max_chunk && chunk <= ((ksteps + 7) / 8) * 8; chunk += 8) {
+  for (int chunk = kGemmU; chunk <= max_chunk && chunk <= ksteps; chunk += kGemmU) {
     const int S = (ksteps + chunk - 1) / chunk;
-    const int chunk_bal = (ksteps + S - 1) / S;  // spread the steps evenly over the S chunks
+    // spread the batches of kGemmU steps as evenly as possible over the S chunks
+    const int batches = ksteps / kGemmU;
+    const int chunk_bal = ((batches + S - 1) / S) * kGemmU;
     if ((S - 1) * chunk_bal >= ksteps) continue;
     const size_t lds = (size_t)chunk_bal * nb * 1024;
     int resident = (int)((160 * 1024) / (lds > 0 ? lds : 1));
@@ -167,6 +170,10 @@ WsLayout ws_layout(const specasr_ctx *ctx, int batch) {
   const size_t nblk = (size_t)logits_argmax_blocks(c.vocab);
   L.blk_val = take(R * nblk * 4);
   L.blk_idx = take(R * nblk * 4);
+  L.qb = take(R * dq * 2);
+  const size_t mc = (size_t)tree_attention_max_chunks(c.n_kv_heads);
+  L.attn_o = take(mc * R * dq * 4);
+  L.attn_ml = take(mc * R * c.n_heads * 2 * 4);
   L.total = off;
   return L;
 }
@@ -174,6 +181,8 @@ WsLayout ws_layout(const specasr_ctx *ctx, int batch) {
 // Host-side view of one call: validated and flattened tree metadata.
 struct HostStep {
   int rows = 0, batch = 0;
+  int max_total_keys = 0;  // max over sequences of kv_len + n_nodes
+  int max_seq_nodes = 0;
   std::vector<int32_t> words;  // the block copied to the device
 };
 
@@ -228,6 +237,8 @@ void build_step(const specasr_ctx *ctx, const specasr_tree *tree, int batch, con
     kvl[b] = L;
     row_start[b] = r;
     n_nodes[b] = n;
+    if (L + n > hs->max_total_keys) hs->max_total_keys = L + n;
+    if (n > hs->max_seq_nodes) hs->max_seq_nodes = n;
     for (int i = 0; i < n; ++i, ++r) {
       const int p = par[i];
       token[r] = tok[i];
@@ -385,8 +396,8 @@ void gemm_stage(specasr_ctx *ctx, int stage, bool profiled_layer, const PackedMa
 // accumulators stay fp32; only the MFMA operands (normalised activations, attention output,
 // SwiGLU output) are rounded to bf16.
 void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_kv *kv,
-                  const specasr_tree *tree, char *ws, const WsLayout &L, int32_t *argmax_dev,
-                  float *logits_dev, hipStream_t st) {
+                  const specasr_tree *tree, char *ws, const WsLayout &L, const HostStep &hs,
+                  int32_t *argmax_dev, float *logits_dev, hipStream_t st) {
   const ModelDims &md = ctx->md;
   const int d = md.d_model, F = md.d_ffn, V = md.vocab, R = m.rows;
   const int dq = md.n_heads * md.head_dim;
@@ -395,6 +406,8 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
   float *part = (float *)(ws + L.part);
   uint16_t *hb = (uint16_t *)(ws + L.hb), *attb = (uint16_t *)(ws + L.attb), *tb = (uint16_t *)(ws + L.tb);
   float2 *cs = (float2 *)(ws + L.rope);
+  uint16_t *qb = (uint16_t *)(ws + L.qb);
+  const bool mfma_attn = tree_attention_supported(md.head_dim);
   const PackedLayer &p0 = ctx->packed[0];
   const GemmPlan pl_qkv = plan_gemm(p0.qkv.n_bands, p0.qkv.ksteps, nb);
   const GemmPlan pl_o = plan_gemm(p0.o.n_bands, p0.o.ksteps, nb);
@@ -420,9 +433,15 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
     const PackedLayer &pk = ctx->packed[l];
     launch_residual_norm(x, part, pending, R, pending_ld, lw.attn_norm, d, md.rms_eps, hb, st);
     gemm_stage(ctx, SPECASR_STAGE_QKV, pl, pk.qkv, hb, d, R, part, pl_qkv, st);
-    launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, ctx->col_k, ctx->col_v, cs, q, kv->k, kv->v, st);
-    launch_attention_generic(m, md, g, l, q, kv->k, kv->v, att, st);
-    launch_to_bf16(att, (int64_t)R * dq, attb, st);
+    if (mfma_attn) {
+      launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, ctx->col_k, ctx->col_v, cs, nullptr, qb, kv->k, kv->v, st);
+      launch_tree_attention(m, md, g, l, hs.max_total_keys, hs.max_seq_nodes, qb, kv->k, kv->v,
+                            (float *)(ws + L.attn_o), (float *)(ws + L.attn_ml), attb, st);
+    } else {
+      launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, ctx->col_k, ctx->col_v, cs, q, nullptr, kv->k, kv->v, st);
+      launch_attention_generic(m, md, g, l, q, kv->k, kv->v, att, st);
+      launch_to_bf16(att, (int64_t)R * dq, attb, st);
+    }
     gemm_stage(ctx, SPECASR_STAGE_O, pl, pk.o, attb, dq, R, part, pl_o, st);
     launch_residual_norm(x, part, pl_o.n_splits, R, pk.o.ldo, lw.ffn_norm, d, md.rms_eps, hb, st);
     gemm_stage(ctx, SPECASR_STAGE_GATE_UP, pl, pk.gu, hb, d, R, part, pl_gu, st);
@@ -443,7 +462,7 @@ specasr_status forward_common(specasr_ctx *ctx, specasr_kv *kv, const specasr_tr
   KvGeom g{kv->capacity, ctx->md.n_layers, ctx->md.n_kv_heads, ctx->md.head_dim};
   StepMeta m = device_meta(ctx, ws, L, hs.batch, hs);
   if (ctx->fast && m.rows <= 64)
-    forward_fast(ctx, m, g, kv, tree, ws, L, argmax_dev, logits_dev, st);
+    forward_fast(ctx, m, g, kv, tree, ws, L, hs, argmax_dev, logits_dev, st);
   else
     forward_generic(ctx, m, g, kv, tree, ws, L, argmax_dev, logits_dev, st);
   HIP_TRY(ctx, hipGetLastError());
@@ -458,9 +477,10 @@ specasr_status build_packed(specasr_ctx *ctx) {
   HIP_TRY(ctx, gemm_skinny_set_lds_limit());
   auto alloc = [&](PackedMatrix &pm, int n_out_padded, int K) -> hipError_t {
     pm.n_bands = n_out_padded / 32;
-    pm.ksteps = K / 16;
+    pm.ksteps = (K / 16 + kGemmU - 1) / kGemmU * kGemmU;
+    pm.k_real = K;
     pm.ldo = n_out_padded;
-    hipError_t e = hipMalloc(&pm.data, (size_t)n_out_padded * K * 2);
+    hipError_t e = hipMalloc(&pm.data, (size_t)n_out_padded * pm.ksteps * 16 * 2);
     if (e == hipSuccess) ctx->owned.push_back(pm.data);
     return e;
   };
@@ -473,20 +493,20 @@ specasr_status build_packed(specasr_ctx *ctx) {
     const specasr_layer_weights &lw = ctx->layers[l];
     PackedLayer &pk = ctx->packed[l];
     HIP_TRY(ctx, alloc(pk.qkv, ctx->col_v + pad32(dkv), d));
-    launch_repack(lw.wq, dq, d, pk.qkv.data, 0, st);
-    launch_repack(lw.wk, dkv, d, pk.qkv.data, ctx->col_k / 32, st);
-    launch_repack(lw.wv, dkv, d, pk.qkv.data, ctx->col_v / 32, st);
+    launch_repack(lw.wq, dq, d, pk.qkv.ksteps, pk.qkv.data, 0, st);
+    launch_repack(lw.wk, dkv, d, pk.qkv.ksteps, pk.qkv.data, ctx->col_k / 32, st);
+    launch_repack(lw.wv, dkv, d, pk.qkv.ksteps, pk.qkv.data, ctx->col_v / 32, st);
     HIP_TRY(ctx, alloc(pk.o, pad32(d), dq));
-    launch_repack(lw.wo, d, dq, pk.o.data, 0, st);
+    launch_repack(lw.wo, d, dq, pk.o.ksteps, pk.o.data, 0, st);
     HIP_TRY(ctx, alloc(pk.gu, 2 * pad32(F), d));
-    launch_repack(lw.w_gate, F, d, pk.gu.data, 0, st);
-    launch_repack(lw.w_up, F, d, pk.gu.data, ctx->col_up / 32, st);
+    launch_repack(lw.w_gate, F, d, pk.gu.ksteps, pk.gu.data, 0, st);
+    launch_repack(lw.w_up, F, d, pk.gu.ksteps, pk.gu.data, ctx->col_up / 32, st);
     HIP_TRY(ctx, alloc(pk.down, pad32(d), F));
-    launch_repack(lw.w_down, d, F, pk.down.data, 0, st);
+    launch_repack(lw.w_down, d, F, pk.down.ksteps, pk.down.data, 0, st);
     HIP_TRY(ctx, hipGetLastError());
   }
   HIP_TRY(ctx, alloc(ctx->lm_head, pad32(c.vocab), d));
-  launch_repack(ctx->w.lm_head, c.vocab, d, ctx->lm_head.data, 0, st);
+  launch_repack(ctx->w.lm_head, c.vocab, d, ctx->lm_head.ksteps, ctx->lm_head.data, 0, st);
   HIP_TRY(ctx, hipGetLastError());
   HIP_TRY(ctx, hipStreamSynchronize(st));
   // bound of the partial-sum buffer: floats per activation row, over every GEMM and both widths

@@ -1,0 +1,259 @@
+// Tree-masked attention for gfx950 with bf16 MFMA (Sec. II-B: 2D attention mask over the draft
+// token tree; Sec. IV-C: used to verify the two-pass sparse tree).
+//
+// Every tree node attends to the cached prefix [0, kv_len) and to the cache slots of the nodes
+// on its own root path.  The KV cache is streamed exactly once per KV head: one wavefront takes
+// (sequence, KV head, chunk of keys) and serves ALL query rows that share the head (the
+// grouped-query heads times the tree nodes), 32 queries per MFMA column block.
+//
+//   S^T[key][query] = K[key][:] . Q[query][:]      A = K tile (rows = keys, read straight from
+//                                                   the cache, 16 B per lane), B = Q^T
+//   online softmax per query column (fp32; max and sum via one cross-half shuffle)
+//   O^T[c][query]  += V^T[c][key] * P^T[key][query] A = V^T gathered from an LDS copy of the V
+//                                                   tile with key pairs interleaved, B = P^T,
+//                                                   which is exactly how the lanes already hold P
+//
+// Partial (unnormalised) outputs per key chunk are merged by a second small kernel.
+#include "kernels.h"
+#include "kernels_mfma.h"
+
+namespace specasr {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  return (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
+}
+
+// grid (n_chunks, Hkv * n_rgb, batch), block 64.  RGW = query row groups (of 32) per wavefront.
+template <int HD, int RGW>
+__global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g, int layer, int H,
+                                                            int Hkv, int n_rgb,
+                                                            const uint16_t *__restrict__ qb,
+                                                            const uint16_t *__restrict__ kc,
+                                                            const uint16_t *__restrict__ vc,
+                                                            int chunk_keys, float *__restrict__ o_part,
+                                                            float *__restrict__ ml_part) {
+  constexpr int KK = HD / 16;  // MFMA k-steps across the head dimension
+  constexpr int CB = HD / 32;  // 32-wide output column blocks
+  __shared__ uint32_t vp[16 * HD];  // V tile: [key pair][column], low half = even key
+  const int lane = threadIdx.x, h = lane >> 5, ql = lane & 31;
+  const int chunk = blockIdx.x, kvh = blockIdx.y / n_rgb, rgb = blockIdx.y % n_rgb, seq = blockIdx.z;
+  const int G = H / Hkv;
+  const int L = m.kv_len[seq], n = m.n_nodes[seq], r0 = m.row_start[seq], rows = m.rows;
+  const int T = L + n, QR = G * n;
+  const int t_begin = chunk * chunk_keys;
+  if (t_begin >= T || rgb * RGW * 32 >= QR) return;
+  const int t_end = min(T, t_begin + chunk_keys);
+
+  // queries of this wavefront
+  bool valid[RGW];
+  int out_row[RGW], out_head[RGW];
+  uint64_t anc[RGW];
+  u32x4 qreg[RGW][KK];
+#pragma unroll
+  for (int w = 0; w < RGW; ++w) {
+    const int qrow = (rgb * RGW + w) * 32 + ql;
+    valid[w] = qrow < QR;
+    const int gi = valid[w] ? qrow / n : 0, node = valid[w] ? qrow - gi * n : 0;
+    out_row[w] = r0 + node;
+    out_head[w] = kvh * G + gi;
+    anc[w] = valid[w] ? m.anc[out_row[w]] : 0ull;
+    const uint16_t *qp = qb + ((int64_t)out_row[w] * H + out_head[w]) * HD + 8 * h;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+      qreg[w][kk] = valid[w] ? *reinterpret_cast<const u32x4 *>(qp + 16 * kk) : (u32x4){0u, 0u, 0u, 0u};
+  }
+  float m_run[RGW], l_run[RGW];
+  f32x16 o[RGW][CB];
+#pragma unroll
+  for (int w = 0; w < RGW; ++w) {
+    m_run[w] = -INFINITY;
+    l_run[w] = 0.f;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) o[w][cb][j] = 0.f;
+  }
+  const uint16_t *kbase = kc + g.row(seq, layer, kvh, 0);
+  const uint16_t *vbase = vc + g.row(seq, layer, kvh, 0);
+
+  for (int t0 = t_begin; t0 < t_end; t0 += 32) {
+    // K tile straight into A-operand registers (keys past the end re-read the last key; masked below)
+    u32x4 kreg[KK];
+    {
+      const uint16_t *kp = kbase + (int64_t)min(t0 + ql, T - 1) * HD + 8 * h;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) kreg[kk] = *reinterpret_cast<const u32x4 *>(kp + 16 * kk);
+    }
+    // V tile into LDS, two keys interleaved per 32-bit word
+    __syncthreads();
+    for (int it = lane; it < 16 * (HD / 8); it += 64) {
+      const int pair = it / (HD / 8), cg = it - pair * (HD / 8);
+      const int k0 = min(t0 + 2 * pair, T - 1), k1 = min(t0 + 2 * pair + 1, T - 1);
+      const u32x4 a = *reinterpret_cast<const u32x4 *>(vbase + (int64_t)k0 * HD + 8 * cg);
+      const u32x4 b = *reinterpret_cast<const u32x4 *>(vbase + (int64_t)k1 * HD + 8 * cg);
+      u32x4 lo, hi;  // columns 8cg..8cg+3 and 8cg+4..8cg+7
+      lo[0] = (a[0] & 0xffffu) | (b[0] << 16);
+      lo[1] = (a[0] >> 16) | (b[0] & 0xffff0000u);
+      lo[2] = (a[1] & 0xffffu) | (b[1] << 16);
+      lo[3] = (a[1] >> 16) | (b[1] & 0xffff0000u);
+      hi[0] = (a[2] & 0xffffu) | (b[2] << 16);
+      hi[1] = (a[2] >> 16) | (b[2] & 0xffff0000u);
+      hi[2] = (a[3] & 0xffffu) | (b[3] << 16);
+      hi[3] = (a[3] >> 16) | (b[3] & 0xffff0000u);
+      u32x4 *dst = reinterpret_cast<u32x4 *>(vp + pair * HD + 8 * cg);
+      dst[0] = lo;
+      dst[1] = hi;
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int w = 0; w < RGW; ++w) {
+      f32x16 sT;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) sT[j] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[kk]),
+                                                     __builtin_bit_cast(bf16x8, qreg[w][kk]), sT, 0, 0, 0);
+      // lane holds, for query ql, the keys t0 + 8*(j/4) + 4*h + j%4
+      float mx = -INFINITY;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int key = t0 + 8 * (j >> 2) + 4 * h + (j & 3);
+        const bool vis = valid[w] && key < T && (key < L || ((anc[w] >> ((key - L) & 63)) & 1ull));
+        sT[j] = vis ? sT[j] : -INFINITY;
+        mx = fmaxf(mx, sT[j]);
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run[w], mx);
+      const bool any = m_new != -INFINITY;
+      const float alpha = (m_run[w] == -INFINITY) ? 0.f : __expf(m_run[w] - m_new);
+      float p[16], psum = 0.f;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        p[j] = (any && sT[j] != -INFINITY) ? __expf(sT[j] - m_new) : 0.f;
+        psum += p[j];
+      }
+      psum += __shfl_xor(psum, 32, 64);
+      l_run[w] = l_run[w] * alpha + psum;
+      m_run[w] = m_new;
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) o[w][cb][j] *= alpha;
+      // P^T as B operand: MFMA mm covers keys 16*mm .. 16*mm+15 of the tile; this lane's k-slots
+      // i = 0..7 are keys 16*mm + 8*(i/4) + 4*h + i%4, i.e. its own p[8*mm + i]
+#pragma unroll
+      for (int mm = 0; mm < 2; ++mm) {
+        u32x4 pb;
+#pragma unroll
+        for (int i2 = 0; i2 < 4; ++i2) pb[i2] = pack_bf16(p[8 * mm + 2 * i2], p[8 * mm + 2 * i2 + 1]);
+        // matching V^T k-slots: key pairs 8*mm + 2*h, +1, 8*mm + 4 + 2*h, +1
+        const uint32_t *vrow = vp + (8 * mm + 2 * h) * HD + ql;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+          u32x4 va;
+          va[0] = vrow[32 * cb];
+          va[1] = vrow[32 * cb + HD];
+          va[2] = vrow[32 * cb + 4 * HD];
+          va[3] = vrow[32 * cb + 5 * HD];
+          o[w][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va),
+                                                             __builtin_bit_cast(bf16x8, pb), o[w][cb], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // partial results: O^T lane layout = query column ql, output columns 32*cb + 8*(j/4) + 4*h + j%4
+#pragma unroll
+  for (int w = 0; w < RGW; ++w) {
+    if (!valid[w]) continue;
+    const int64_t base = ((int64_t)chunk * rows + out_row[w]) * H + out_head[w];
+    float *op = o_part + base * HD + 4 * h;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4)
+        *reinterpret_cast<float4 *>(op + 32 * cb + 8 * q4) =
+            make_float4(o[w][cb][4 * q4], o[w][cb][4 * q4 + 1], o[w][cb][4 * q4 + 2], o[w][cb][4 * q4 + 3]);
+    if (h == 0) {
+      ml_part[base * 2] = m_run[w];
+      ml_part[base * 2 + 1] = l_run[w];
+    }
+  }
+}
+
+// Merge the key chunks: out = sum_c e^(m_c - M) o_c / sum_c e^(m_c - M) l_c, rounded to bf16.
+// grid (H, rows), block HD.
+__global__ void tree_attention_merge_kernel(StepMeta m, int H, int HD, int chunk_keys,
+                                            const float *__restrict__ o_part,
+                                            const float *__restrict__ ml_part,
+                                            uint16_t *__restrict__ out) {
+  const int a = blockIdx.x, r = blockIdx.y, c = threadIdx.x, rows = m.rows;
+  const int seq = m.seq[r];
+  const int T = m.kv_len[seq] + m.n_nodes[seq];
+  const int n_chunks = (T + chunk_keys - 1) / chunk_keys;
+  float M = -INFINITY;
+  for (int ch = 0; ch < n_chunks; ++ch) M = fmaxf(M, ml_part[(((int64_t)ch * rows + r) * H + a) * 2]);
+  float num = 0.f, den = 0.f;
+  for (int ch = 0; ch < n_chunks; ++ch) {
+    const int64_t base = ((int64_t)ch * rows + r) * H + a;
+    const float mc = ml_part[base * 2];
+    const float wgt = (mc == -INFINITY) ? 0.f : __expf(mc - M);
+    num += wgt * o_part[base * HD + c];
+    den += wgt * ml_part[base * 2 + 1];
+  }
+  out[((int64_t)r * H + a) * HD + c] = f32_to_bf16_bits(num / den);
+}
+
+template <int HD>
+static void launch_attn_hd(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
+                           int max_seq_nodes, int chunk_keys, int n_chunks, const uint16_t *qb,
+                           const void *kc, const void *vc, float *o_part, float *ml_part,
+                           uint16_t *out, hipStream_t st) {
+  const int G = md.n_heads / md.n_kv_heads;
+  const int row_groups = (G * max_seq_nodes + 31) / 32;
+  if (row_groups <= 1) {
+    dim3 grid(n_chunks, md.n_kv_heads, m.batch);
+    tree_attention_kernel<HD, 1><<<grid, 64, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, 1, qb, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, o_part, ml_part);
+  } else {
+    const int n_rgb = (row_groups + 1) / 2;
+    dim3 grid(n_chunks, md.n_kv_heads * n_rgb, m.batch);
+    tree_attention_kernel<HD, 2><<<grid, 64, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, n_rgb, qb, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, o_part, ml_part);
+  }
+  dim3 mgrid(md.n_heads, m.rows);
+  tree_attention_merge_kernel<<<mgrid, HD, 0, st>>>(m, md.n_heads, HD, chunk_keys, o_part, ml_part, out);
+}
+
+bool tree_attention_supported(int head_dim) { return head_dim == 64 || head_dim == 128; }
+
+int tree_attention_max_chunks(int n_kv_heads) { return 512 / n_kv_heads + 2; }
+
+// Key-chunk size (a multiple of 32) aiming at ~512 wavefronts for the longest sequence.
+int tree_attention_chunk_keys(int max_total_keys, int n_kv_heads, int batch, int row_group_blocks) {
+  long want = ((long)max_total_keys * n_kv_heads * batch * row_group_blocks + 511) / 512;
+  long ck = (want + 31) / 32 * 32;
+  if (ck < 32) ck = 32;
+  return (int)ck;
+}
+
+void launch_tree_attention(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
+                           int max_total_keys, int max_seq_nodes, const uint16_t *qb,
+                           const void *kc, const void *vc, float *o_part, float *ml_part,
+                           uint16_t *out, hipStream_t st) {
+  const int G = md.n_heads / md.n_kv_heads;
+  const int row_groups = (G * max_seq_nodes + 31) / 32;
+  const int n_rgb = row_groups <= 1 ? 1 : (row_groups + 1) / 2;
+  const int ck = tree_attention_chunk_keys(max_total_keys, md.n_kv_heads, m.batch, n_rgb);
+  const int n_chunks = (max_total_keys + ck - 1) / ck;
+  if (md.head_dim == 64)
+    launch_attn_hd<64>(m, md, g, layer, max_seq_nodes, ck, n_chunks, qb, kc, vc, o_part, ml_part, out, st);
+  else
+    launch_attn_hd<128>(m, md, g, layer, max_seq_nodes, ck, n_chunks, qb, kc, vc, o_part, ml_part, out, st);
+}
+
+}  // namespace specasr

@@ -5,12 +5,14 @@
 namespace specasr {
 
 constexpr int kGemmMaxLds = 96 * 1024;  // LDS bytes one skinny-GEMM workgroup may use for activations
+constexpr int kGemmU = 8;                // weight tiles each lane keeps in flight; k-chunks are multiples of it
 
 // A weight matrix repacked into MFMA A-operand tiles: [n_bands][ksteps][64 lanes][8 bf16].
 struct PackedMatrix {
   void *data = nullptr;
   int n_bands = 0;  // bands of 32 output features (last one zero padded)
-  int ksteps = 0;   // in_features / 16
+  int ksteps = 0;   // k-steps of 16 input features, padded with zero tiles to a multiple of kGemmU
+  int k_real = 0;   // in_features
   int ldo = 0;      // n_bands * 32: row stride of the partial-sum output
 };
 
@@ -20,7 +22,8 @@ struct GemmPlan {
   int bands_per_wave = 1;  // bands each wavefront streams
 };
 
-void launch_repack(const void *src, int n_out, int K, void *dst, int band0, hipStream_t st);
+void launch_repack(const void *src, int n_out, int K, int ksteps_pad, void *dst, int band0,
+                   hipStream_t st);
 hipError_t gemm_skinny_set_lds_limit();
 void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *X, int ldx, int rows, float *part,
                         const GemmPlan &plan, hipStream_t st);
@@ -28,7 +31,8 @@ void launch_residual_norm(float *x, const float *part, int n_splits, int rows, i
                           const void *gain, int d, float eps, uint16_t *hb, hipStream_t st);
 void launch_qkv_finish(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
                        const float *part, int n_splits, int ldp, int col_k, int col_v,
-                       const float2 *cs, float *q, void *kc, void *vc, hipStream_t st);
+                       const float2 *cs, float *q, uint16_t *qb, void *kc, void *vc,
+                       hipStream_t st);
 void launch_swiglu_finish(const float *part, int n_splits, int rows, int ldp, int col_up, int F,
                           uint16_t *t, hipStream_t st);
 void launch_to_bf16(const float *src, int64_t n, uint16_t *dst, hipStream_t st);
@@ -36,5 +40,13 @@ int logits_argmax_blocks(int V);
 void launch_logits_argmax(const StepMeta &m, const float *part, int n_splits, int ldp, int V,
                           int max_nodes, float *logits_out, float *blk_val, int *blk_idx,
                           int32_t *argmax, hipStream_t st);
+
+// tree-masked MFMA attention (kernels_attn.hip)
+bool tree_attention_supported(int head_dim);
+int tree_attention_max_chunks(int n_kv_heads);
+void launch_tree_attention(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
+                           int max_total_keys, int max_seq_nodes, const uint16_t *qb,
+                           const void *kc, const void *vc, float *o_part, float *ml_part,
+                           uint16_t *out, hipStream_t st);
 
 }  // namespace specasr

@@ -27,106 +27,106 @@ __device__ __forceinline__ u32x4 load_stream(const u32x4 *p) { return __builtin_
 
 // --------------------------------------------------------------------------- weight repack
 // dst tile (band, kt), lane l, element i  <-  src[band*32 + l%32][kt*16 + 8*(l/32) + i]
-// Rows >= n_out (padding of the last band) are zero.  `row0` is the first packed row written,
-// so several source matrices can be concatenated band-aligned into one packed matrix.
-__global__ void repack_kernel(const uint16_t *src, int n_out, int K, uint16_t *dst, int band0) {
-  const int ksteps = K / 16;
-  const int64_t tile = blockIdx.x;  // over (n_out padded / 32) * ksteps
-  const int band = (int)(tile / ksteps), kt = (int)(tile - (int64_t)band * ksteps);
+// Rows >= n_out (padding of the last band) and columns >= K (padding of k to a whole number of
+// kGemmU-tile batches) are zero.  `band0` is the first packed band written, so several source
+// matrices can be concatenated band-aligned into one packed matrix.
+__global__ void repack_kernel(const uint16_t *src, int n_out, int K, int ksteps_pad, uint16_t *dst,
+                              int band0) {
+  const int64_t tile = blockIdx.x;  // over bands * ksteps_pad
+  const int band = (int)(tile / ksteps_pad), kt = (int)(tile - (int64_t)band * ksteps_pad);
   const int l = threadIdx.x;  // 64 lanes
   const int row = band * 32 + (l & 31);
+  const int col = kt * 16 + 8 * (l >> 5);
   u32x4 v = (u32x4){0u, 0u, 0u, 0u};
-  if (row < n_out) v = *reinterpret_cast<const u32x4 *>(src + (int64_t)row * K + kt * 16 + 8 * (l >> 5));
-  reinterpret_cast<u32x4 *>(dst)[((int64_t)(band0 + band) * ksteps + kt) * 64 + l] = v;
+  if (row < n_out && col < K) v = *reinterpret_cast<const u32x4 *>(src + (int64_t)row * K + col);
+  reinterpret_cast<u32x4 *>(dst)[((int64_t)(band0 + band) * ksteps_pad + kt) * 64 + l] = v;
 }
 
-void launch_repack(const void *src, int n_out, int K, void *dst, int band0, hipStream_t st) {
+void launch_repack(const void *src, int n_out, int K, int ksteps_pad, void *dst, int band0,
+                   hipStream_t st) {
   const int bands = (n_out + 31) / 32;
-  const int64_t tiles = (int64_t)bands * (K / 16);
-  repack_kernel<<<(unsigned)tiles, 64, 0, st>>>((const uint16_t *)src, n_out, K, (uint16_t *)dst, band0);
+  const int64_t tiles = (int64_t)bands * ksteps_pad;
+  repack_kernel<<<(unsigned)tiles, 64, 0, st>>>((const uint16_t *)src, n_out, K, ksteps_pad, (uint16_t *)dst, band0);
 }
 
 // --------------------------------------------------------------------------- skinny GEMM
 // part[s][row][o] = sum over k in chunk s of X[row][k] * W[o][k]
 // grid.x = n_splits * n_groups; block = 256 (4 wavefronts); wavefront w of group g owns bands
 // [(g*4+w)*bpw, +bpw).  LDS: X chunk in B-operand order, [kstep][NB][64 lanes] x 16 bytes.
+// Every chunk holds a whole number of U-tile batches (the packed k extent is padded to that), so
+// the steady-state loop is branch-free: U unconditional loads stay in flight per lane, the ring
+// runs on across band boundaries, and at the very end it re-reads the last batch (unused).
 template <int NB, int U>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4 *__restrict__ Wp,
                                                           const uint16_t *__restrict__ X, int ldx,
-                                                          float *__restrict__ part, int ldo,
+                                                          int K, float *__restrict__ part, int ldo,
                                                           int rows, int n_bands, int ksteps_all,
                                                           int n_splits, int chunk_steps, int bpw) {
   extern __shared__ u32x4 lds[];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int s = blockIdx.x % n_splits, grp = blockIdx.x / n_splits;
   const int ks0 = s * chunk_steps;
-  const int nks = min(chunk_steps, ksteps_all - ks0);  // k-steps of this chunk
+  const int nks = min(chunk_steps, ksteps_all - ks0);  // k-steps of this chunk, a multiple of U
   const int b0 = min((grp * 4 + wave) * bpw, n_bands), b1 = min(b0 + bpw, n_bands);
-  const int nblk = (b1 - b0) * nks;
+  const u32x4 *wbase = Wp + (int64_t)ks0 * 64 + lane;
+  const int64_t band_stride = (int64_t)ksteps_all * 64;
 
   // start the weight stream before anything else
   u32x4 buf[U];
-  int pf_band = b0, pf_k = 0, issued = 0;  // next tile to prefetch
-  auto tile_ptr = [&](int band, int k) { return Wp + ((int64_t)band * ksteps_all + ks0 + k) * 64 + lane; };
+  {
+    const u32x4 *p = wbase + (int64_t)min(b0, n_bands - 1) * band_stride;
 #pragma unroll
-  for (int u = 0; u < U; ++u) {
-    buf[u] = (u32x4){0u, 0u, 0u, 0u};
-    if (issued < nblk) {
-      buf[u] = load_stream(tile_ptr(pf_band, pf_k));
-      ++issued;
-      if (++pf_k == nks) { pf_k = 0; ++pf_band; }
-    }
+    for (int u = 0; u < U; ++u) buf[u] = load_stream(p + 64 * u);
   }
   // stage the activation chunk: slot (kstep, nb, l) <- X[nb*32 + l%32][16*(ks0+kstep) + 8*(l/32) ..+7]
   for (int idx = threadIdx.x; idx < nks * NB * 64; idx += 256) {
     const int l = idx & 63, blk = idx >> 6;
     const int nb = blk % NB, kstep = blk / NB;
     const int r = nb * 32 + (l & 31);
+    const int col = 16 * (ks0 + kstep) + 8 * (l >> 5);
     u32x4 v = (u32x4){0u, 0u, 0u, 0u};
-    if (r < rows) v = *reinterpret_cast<const u32x4 *>(X + (int64_t)r * ldx + 16 * (ks0 + kstep) + 8 * (l >> 5));
+    if (r < rows && col < K) v = *reinterpret_cast<const u32x4 *>(X + (int64_t)r * ldx + col);
     lds[idx] = v;
   }
   __syncthreads();
 
-  f32x16 acc[NB];
+  for (int band = b0; band < b1; ++band) {
+    // two accumulator sets per node group: consecutive tiles do not wait on each other
+    f32x16 acc[NB][2];
 #pragma unroll
-  for (int n = 0; n < NB; ++n)
+    for (int n = 0; n < NB; ++n)
 #pragma unroll
-    for (int j = 0; j < 16; ++j) acc[n][j] = 0.f;
-  int k = 0, band = b0;
-  for (int done = 0; done < nblk; done += U) {
+      for (int h = 0; h < 2; ++h)
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (done + u < nblk) {
+        for (int j = 0; j < 16; ++j) acc[n][h][j] = 0.f;
+    for (int kb = 0; kb < nks; kb += U) {
+      // where the next batch of this wavefront's stream lives
+      int nband = band, nk = kb + U;
+      if (nk >= nks) { nk = 0; ++nband; }
+      if (nband >= b1) { nband = band; nk = kb; }
+      const u32x4 *pn = wbase + (int64_t)nband * band_stride + (int64_t)nk * 64;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
         const bf16x8 a = __builtin_bit_cast(bf16x8, buf[u]);
-        if (issued < nblk) {
-          buf[u] = load_stream(tile_ptr(pf_band, pf_k));
-          ++issued;
-          if (++pf_k == nks) { pf_k = 0; ++pf_band; }
-        }
 #pragma unroll
         for (int n = 0; n < NB; ++n) {
-          const bf16x8 b = __builtin_bit_cast(bf16x8, lds[(k * NB + n) * 64 + lane]);
-          acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[n], 0, 0, 0);
+          const bf16x8 b = __builtin_bit_cast(bf16x8, lds[((kb + u) * NB + n) * 64 + lane]);
+          acc[n][u & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[n][u & 1], 0, 0, 0);
         }
-        if (++k == nks) {
-          // C layout: lane l holds node column l%32 and output rows 8*(j/4) + 4*(l/32) + j%4
+        buf[u] = load_stream(pn + 64 * u);  // refill the slot just consumed
+      }
+    }
+    // C layout: lane l holds node column l%32 and output rows 8*(j/4) + 4*(l/32) + j%4
 #pragma unroll
-          for (int n = 0; n < NB; ++n) {
-            const int r = n * 32 + (lane & 31);
-            if (r < rows) {
-              float *dst = part + ((int64_t)s * rows + r) * ldo + band * 32 + 4 * (lane >> 5);
+    for (int n = 0; n < NB; ++n) {
+      const int r = n * 32 + (lane & 31);
+      if (r < rows) {
+        float *dst = part + ((int64_t)s * rows + r) * ldo + band * 32 + 4 * (lane >> 5);
 #pragma unroll
-              for (int q = 0; q < 4; ++q)
-                *reinterpret_cast<float4 *>(dst + 8 * q) =
-                    make_float4(acc[n][4 * q], acc[n][4 * q + 1], acc[n][4 * q + 2], acc[n][4 * q + 3]);
-            }
-#pragma unroll
-            for (int j = 0; j < 16; ++j) acc[n][j] = 0.f;
-          }
-          k = 0;
-          ++band;
-        }
+        for (int q = 0; q < 4; ++q)
+          *reinterpret_cast<float4 *>(dst + 8 * q) =
+              make_float4(acc[n][0][4 * q] + acc[n][1][4 * q], acc[n][0][4 * q + 1] + acc[n][1][4 * q + 1],
+                          acc[n][0][4 * q + 2] + acc[n][1][4 * q + 2], acc[n][0][4 * q + 3] + acc[n][1][4 * q + 3]);
       }
     }
   }
@@ -139,31 +139,44 @@ void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *X, int ldx, int r
   const int nb = rows <= 32 ? 1 : 2;
   const size_t lds = (size_t)plan.chunk_steps * nb * 64 * 16;
   if (nb == 1)
-    gemm_skinny_kernel<1, 8><<<grid, 256, lds, st>>>((const u32x4 *)W.data, X, ldx, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits, plan.chunk_steps, plan.bands_per_wave);
+    gemm_skinny_kernel<1, kGemmU><<<grid, 256, lds, st>>>((const u32x4 *)W.data, X, ldx, W.k_real, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits, plan.chunk_steps, plan.bands_per_wave);
   else
-    gemm_skinny_kernel<2, 8><<<grid, 256, lds, st>>>((const u32x4 *)W.data, X, ldx, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits, plan.chunk_steps, plan.bands_per_wave);
+    gemm_skinny_kernel<2, kGemmU><<<grid, 256, lds, st>>>((const u32x4 *)W.data, X, ldx, W.k_real, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits, plan.chunk_steps, plan.bands_per_wave);
 }
 
 hipError_t gemm_skinny_set_lds_limit() {
-  hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<1, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmMaxLds);
+  hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<1, kGemmU>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmMaxLds);
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute((const void *)gemm_skinny_kernel<2, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmMaxLds);
+  return hipFuncSetAttribute((const void *)gemm_skinny_kernel<2, kGemmU>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmMaxLds);
 }
 
 // --------------------------------------------------------------------------- consumers of partial sums
 // x[r][:] += sum_s part[s][r][:]   (n_splits may be 0: plain norm)
 // hb[r][:]  = bf16( x[r][:] * rsqrt(mean(x^2) + eps) * gain )
-__global__ __launch_bounds__(256) void residual_norm_kernel(float *x, const float *part, int n_splits,
-                                                            int rows, int ldp, const uint16_t *gain,
-                                                            int d, float eps, uint16_t *hb) {
+__global__ __launch_bounds__(1024) void residual_norm_kernel(float *x, const float *part, int n_splits,
+                                                             int rows, int ldp, const uint16_t *gain,
+                                                             int d, float eps, uint16_t *hb) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   float *xr = x + (int64_t)r * d;
   float ss = 0.f;
-  for (int c = threadIdx.x * 4; c < d; c += 1024) {
+  for (int c = threadIdx.x * 4; c < d; c += 4096) {
     float4 v = *reinterpret_cast<const float4 *>(xr + c);
-    for (int s = 0; s < n_splits; ++s) {
-      const float4 p = *reinterpret_cast<const float4 *>(part + ((int64_t)s * rows + r) * ldp + c);
+    const float *pp = part + (int64_t)r * ldp + c;
+    const int64_t sstride = (int64_t)rows * ldp;
+    int s = 0;
+    for (; s + 4 <= n_splits; s += 4) {  // four independent loads in flight, summed in split order
+      const float4 p0 = *reinterpret_cast<const float4 *>(pp + (s + 0) * sstride);
+      const float4 p1 = *reinterpret_cast<const float4 *>(pp + (s + 1) * sstride);
+      const float4 p2 = *reinterpret_cast<const float4 *>(pp + (s + 2) * sstride);
+      const float4 p3 = *reinterpret_cast<const float4 *>(pp + (s + 3) * sstride);
+      v.x += p0.x; v.y += p0.y; v.z += p0.z; v.w += p0.w;
+      v.x += p1.x; v.y += p1.y; v.z += p1.z; v.w += p1.w;
+      v.x += p2.x; v.y += p2.y; v.z += p2.z; v.w += p2.w;
+      v.x += p3.x; v.y += p3.y; v.z += p3.z; v.w += p3.w;
+    }
+    for (; s < n_splits; ++s) {
+      const float4 p = *reinterpret_cast<const float4 *>(pp + s * sstride);
       v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
     }
     if (n_splits > 0) *reinterpret_cast<float4 *>(xr + c) = v;
@@ -171,7 +184,7 @@ __global__ __launch_bounds__(256) void residual_norm_kernel(float *x, const floa
   }
   ss = block_sum(ss, red);
   const float rs = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int c = threadIdx.x * 4; c < d; c += 1024) {
+  for (int c = threadIdx.x * 4; c < d; c += 4096) {
     const float4 v = *reinterpret_cast<const float4 *>(xr + c);
     const uint2 g = *reinterpret_cast<const uint2 *>(gain + c);
     uint2 o;
@@ -185,49 +198,59 @@ __global__ __launch_bounds__(256) void residual_norm_kernel(float *x, const floa
 
 void launch_residual_norm(float *x, const float *part, int n_splits, int rows, int ldp,
                           const void *gain, int d, float eps, uint16_t *hb, hipStream_t st) {
-  residual_norm_kernel<<<rows, 256, 0, st>>>(x, part, n_splits, rows, ldp, (const uint16_t *)gain, d, eps, hb);
+  residual_norm_kernel<<<rows, 1024, 0, st>>>(x, part, n_splits, rows, ldp, (const uint16_t *)gain, d, eps, hb);
 }
 
 // q, k, v = sum of partials; rotary embedding at the node's depth position (Sec. II-B: each
-// branch is verified as its own sequence, so position = kv_len + depth); q -> fp32 [rows][H*hd],
-// k, v -> bf16 cache slot kv_len + node.  Packed output columns: [q | pad | k | pad | v].
+// branch is verified as its own sequence, so position = kv_len + depth).  Outputs: q either as
+// fp32 [rows][H*hd] (generic attention) or as bf16 pre-multiplied by 1/sqrt(hd) (MFMA
+// attention); k, v -> bf16 cache slot kv_len + node.  Packed columns: [q | pad | k | pad | v].
 __global__ __launch_bounds__(256) void qkv_finish_kernel(StepMeta m, KvGeom g, int layer, int H, int Hkv,
                                                          int hd, const float *part, int n_splits,
                                                          int ldp, int col_k, int col_v,
-                                                         const float2 *cs, float *q, uint16_t *kc,
-                                                         uint16_t *vc) {
-  const int r = blockIdx.x, half = hd / 2, rows = m.rows;
-  const float2 *csr = cs + (int64_t)r * half;
-  const int seq = m.seq[r];
-  const int64_t slot = m.slot[r];
+                                                         const float2 *cs, float *q, uint16_t *qb,
+                                                         float qscale, uint16_t *kc, uint16_t *vc) {
+  const int r = blockIdx.y, half = hd / 2, rows = m.rows;
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (H + Hkv) * half) return;
+  const int a = idx / half, j = idx - a * half;
+  const float2 c = cs[(int64_t)r * half + j];
+  const float *pr = part + (int64_t)r * ldp;
+  const int64_t sstride = (int64_t)rows * ldp;
   auto val = [&](int col) {
     float v = 0.f;
-    for (int s = 0; s < n_splits; ++s) v += part[((int64_t)s * rows + r) * ldp + col];
+    for (int s = 0; s < n_splits; ++s) v += pr[s * sstride + col];
     return v;
   };
-  for (int idx = threadIdx.x; idx < (H + Hkv) * half; idx += 256) {
-    const int a = idx / half, j = idx - a * half;
-    const float2 c = csr[j];
-    if (a < H) {
-      const float x0 = val(a * hd + j), x1 = val(a * hd + j + half);
-      q[((int64_t)r * H + a) * hd + j] = x0 * c.x - x1 * c.y;
-      q[((int64_t)r * H + a) * hd + j + half] = x1 * c.x + x0 * c.y;
+  if (a < H) {
+    const float x0 = val(a * hd + j), x1 = val(a * hd + j + half);
+    const float y0 = x0 * c.x - x1 * c.y, y1 = x1 * c.x + x0 * c.y;
+    const int64_t o = ((int64_t)r * H + a) * hd + j;
+    if (qb) {
+      qb[o] = f32_to_bf16_bits(y0 * qscale);
+      qb[o + half] = f32_to_bf16_bits(y1 * qscale);
     } else {
-      const int b = a - H;
-      const float x0 = val(col_k + b * hd + j), x1 = val(col_k + b * hd + j + half);
-      const int64_t base = g.row(seq, layer, b, slot);
-      kc[base + j] = f32_to_bf16_bits(x0 * c.x - x1 * c.y);
-      kc[base + j + half] = f32_to_bf16_bits(x1 * c.x + x0 * c.y);
-      vc[base + j] = f32_to_bf16_bits(val(col_v + b * hd + j));
-      vc[base + j + half] = f32_to_bf16_bits(val(col_v + b * hd + j + half));
+      q[o] = y0;
+      q[o + half] = y1;
     }
+  } else {
+    const int b = a - H;
+    const float x0 = val(col_k + b * hd + j), x1 = val(col_k + b * hd + j + half);
+    const int64_t base = g.row(m.seq[r], layer, b, m.slot[r]);
+    kc[base + j] = f32_to_bf16_bits(x0 * c.x - x1 * c.y);
+    kc[base + j + half] = f32_to_bf16_bits(x1 * c.x + x0 * c.y);
+    vc[base + j] = f32_to_bf16_bits(val(col_v + b * hd + j));
+    vc[base + j + half] = f32_to_bf16_bits(val(col_v + b * hd + j + half));
   }
 }
 
 void launch_qkv_finish(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
                        const float *part, int n_splits, int ldp, int col_k, int col_v,
-                       const float2 *cs, float *q, void *kc, void *vc, hipStream_t st) {
-  qkv_finish_kernel<<<m.rows, 256, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, md.head_dim, part, n_splits, ldp, col_k, col_v, cs, q, (uint16_t *)kc, (uint16_t *)vc);
+                       const float2 *cs, float *q, uint16_t *qb, void *kc, void *vc,
+                       hipStream_t st) {
+  const int items = (md.n_heads + md.n_kv_heads) * (md.head_dim / 2);
+  dim3 grid((items + 255) / 256, m.rows);
+  qkv_finish_kernel<<<grid, 256, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, md.head_dim, part, n_splits, ldp, col_k, col_v, cs, q, qb, 1.0f / sqrtf((float)md.head_dim), (uint16_t *)kc, (uint16_t *)vc);
 }
 
 // t[r][f] = bf16( silu(sum_s gate) * (sum_s up) ); gate at column f, up at column col_up + f

@@ -318,3 +318,33 @@ def test_chain_prefill_with_audio_embeddings(dtype, tol):
     err = row_rel_err(fw["logits"][0, n - 1].cpu().numpy()[None], last[None])
     assert err.max() <= tol
     ver.close()
+
+
+@pytest.mark.parametrize("shape", [
+    dict(n_heads=4, n_kv_heads=2, head_dim=64),     # grouped-query, 2 query heads per KV head
+    dict(n_heads=8, n_kv_heads=1, head_dim=64, d_model=512),   # 8 query heads on one KV head
+    dict(n_heads=2, n_kv_heads=2, head_dim=128),    # head_dim 128, multi-head
+    dict(n_heads=4, n_kv_heads=1, head_dim=128, d_model=512),  # head_dim 128, grouped
+    dict(n_heads=8, n_kv_heads=8, head_dim=32),     # head_dim the MFMA attention does not cover
+])
+def test_attention_shapes_bf16(shape):
+    """GQA groupings and head sizes through the bf16 path, trees up to 64 nodes (several 32-query
+    groups per KV head), ragged prefix lengths around the 32-key tile size."""
+    cfg = dict(wl.MODELS["tiny"], **shape)
+    w = wl.make_weights(cfg, 91, "bf16")
+    rng = np.random.default_rng(92)
+    text = rng.integers(0, cfg["vocab"], 200).astype(np.int32)
+    om, kc, vc, Lfull, _ = oracle_prefilled(cfg, w, None, text, 280)
+    ver = _verifier(cfg, w, "bf16", max_nodes=64, capacity=280)
+    for n, L in ((1, 1), (5, 31), (32, 32), (33, 95), (64, 200), (17, 0)):
+        parents = wl.random_tree(rng, n, max_children=3)
+        tokens = rng.integers(0, cfg["vocab"], n).astype(np.int32)
+        ver.set_cache(_store_cache(kc, "bf16"), _store_cache(vc, "bf16"), [L])
+        k0, v0 = ver.get_cache()
+        ref = om.tree_forward(k0[0], v0[0], L, tokens, parents)
+        fw = ver.tree_forward([tokens], [parents])
+        assert fw["status"] == 0
+        check_forward(ref, fw["logits"][0].cpu().numpy(), fw["argmax"][0].cpu().numpy(), TOL_BF16)
+        k1, v1 = ver.get_cache()
+        check_tree_kv(k1[0], v1[0], L, ref, TOL_BF16)
+    ver.close()
