@@ -88,9 +88,10 @@ size_t meta_words(int rows_max, int batch) {
 
 inline int pad32(int v) { return (v + 31) / 32 * 32; }
 
-// Chooses the k-split and the bands per wavefront of one skinny GEMM.  The stage is HBM bound:
-// the cost model counts bytes (weights once, partial sums written and re-read, activations
-// re-staged per workgroup from L2) and the imbalance of the last round of workgroups.
+// Chooses the k-split and the bands per wavefront of one skinny GEMM.  Fitted to a sweep on
+// MI355X: the stage is HBM bound and runs best as about one workgroup per compute unit, each
+// wavefront streaming as long a contiguous span as possible; the model charges rounds of 256
+// workgroups, a fixed start-up per wavefront, and the partial-sum traffic of the k-split.
 GemmPlan plan_gemm(int n_bands, int ksteps, int nb) {
   GemmPlan best;
   double best_cost = 1e300;
@@ -100,27 +101,18 @@ GemmPlan plan_gemm(int n_bands, int ksteps, int nb) {
     // spread the batches of kGemmU steps as evenly as possible over the S chunks
     const int batches = ksteps / kGemmU;
     const int chunk_bal = ((batches + S - 1) / S) * kGemmU;
-    if ((S - 1) * chunk_bal >= ksteps) continue;
-    const size_t lds = (size_t)chunk_bal * nb * 1024;
-    int resident = (int)((160 * 1024) / (lds > 0 ? lds : 1));
-    if (resident > 8) resident = 8;
-    if (resident < 1) continue;
-    for (int bpw = 1; bpw <= 32; ++bpw) {
+    if (chunk_bal != chunk || (S - 1) * chunk_bal >= ksteps) continue;
+    for (int bpw = 1; bpw <= 64; ++bpw) {
       const int groups = (n_bands + 4 * bpw - 1) / (4 * bpw);
       const long wgs = (long)groups * S;
-      const long slots = 256L * resident;
-      const long rounds = (wgs + slots - 1) / slots;
-      const double live = (double)(wgs < slots ? wgs : slots);          // workgroups running at once
-      const double per_wave_kb = (double)bpw * chunk_bal + 24.0;         // stream + start-up latency
-      const double stream = (double)rounds * per_wave_kb * live * 4.0;   // KB-equivalents
-      const double idle = live * 4.0 < 2048.0 ? 2048.0 / (live * 4.0) : 1.0;  // too few waves in flight
-      const double partial = (double)S * 32.0 * nb * n_bands * 32.0 * 4.0 / 1024.0 * 2.5;
-      const double stage = (double)wgs * chunk_bal * nb * 0.5;
-      const double cost = stream * idle + partial + stage;
+      const long rounds = (wgs + 255) / 256;
+      const double stream = (double)rounds * ((double)bpw * chunk + 8.0);
+      const double partial = (double)S * 32.0 * nb * n_bands * 32.0 * 4.0 / 1024.0 * 0.5 / 1024.0;
+      const double cost = stream + partial;
       if (cost < best_cost) {
         best_cost = cost;
         best.n_splits = S;
-        best.chunk_steps = chunk_bal;
+        best.chunk_steps = chunk;
         best.bands_per_wave = bpw;
       }
     }

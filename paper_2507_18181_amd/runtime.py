@@ -75,6 +75,11 @@ class Verifier:
         torch.cuda.synchronize()
         return _to_host(self.k), _to_host(self.v)
 
+    def get_rows(self, lo, hi):
+        """Cache slots [lo, hi) of every sequence/layer/head as host arrays (K, V)."""
+        torch.cuda.synchronize()
+        return (_to_host(self.k[:, :, :, lo:hi].contiguous()), _to_host(self.v[:, :, :, lo:hi].contiguous()))
+
     # -- marshalling helpers ----------------------------------------------------
     def _tree(self, tokens, parents, embeds=None, use_embed=None):
         """tokens/parents: list (one per sequence) of int sequences."""

@@ -1,0 +1,250 @@
+"""GPU parity at the full workload sizes, in the launch configuration bench.py times: the HIP path
+(through the C ABI) against the fp64 oracle on the same seeded weights, cache and trees.
+
+The KV prefix is a directly seeded cache (K, V ~ N(0,1)): the cache is an INPUT of the verify step,
+both sides read the same bf16 bits.  Stand-in for the paper's LibriSpeech / Llama trajectories.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workload as wl
+from parity_util import TOL_BF16, check_forward, check_tree_kv, top2_gap, GAP, widen_cache
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+class _Model:
+    def __init__(self, name, seed):
+        from paper_2507_18181_amd.runtime import upload_weights
+        self.cfg = wl.MODELS[name]
+        self.w_host = wl.make_weights(self.cfg, seed, "bf16", threads=16)
+        self.w_dev = upload_weights(self.w_host, "cuda:0")
+        self.om = oracle.OracleModel(self.cfg, self.w_host)
+
+    def verifier(self, capacity, max_batch=1, flags=0):
+        from paper_2507_18181_amd.runtime import Verifier
+        return Verifier(self.cfg, self.w_dev, "bf16", max_nodes=64, capacity=capacity,
+                        max_batch=max_batch, flags=flags, weights_on_device=True)
+
+
+@pytest.fixture(scope="module")
+def model_1b():
+    m = _Model("1b", wl.WORKLOADS["cfg2_1b_n16"]["seed"])
+    yield m
+    del m
+    torch.cuda.empty_cache()
+
+
+@pytest.fixture(scope="module")
+def model_7b():
+    m = _Model("7b", wl.WORKLOADS["cfg3_7b_n32"]["seed"])
+    yield m
+    del m
+    torch.cuda.empty_cache()
+
+
+def _round_checks(ver, om, tokens, parents, L, b=0):
+    """Full verify round of one sequence against the oracle; returns (out, ref)."""
+    from paper_2507_18181_amd import binding as B
+    n = len(parents)
+    k0, v0 = ver.get_cache()
+    ref = om.tree_forward(np.ascontiguousarray(k0[b]), np.ascontiguousarray(v0[b]), L, tokens, parents)
+    fw = ver.tree_forward([tokens], [parents])
+    assert fw["status"] == 0
+    lg = fw["logits"][b].cpu().numpy()
+    check_forward(ref, lg, fw["argmax"][b].cpu().numpy(), TOL_BF16)
+    k1, v1 = ver.get_cache()
+    check_tree_kv(k1[b], v1[b], L, ref, TOL_BF16)
+    assert np.array_equal(k1[b][:, :, :L], k0[b][:, :, :L])
+    out = ver.verify_tree([tokens], [parents])
+    assert out["status"] == 0
+    path, alen, nxt = oracle.accept(tokens, parents, out["argmax"][b, :n])
+    assert out["accept_len"][b] == alen and out["next_token"][b] == nxt
+    assert out["path"][b, :alen].tolist() == path.tolist()
+    rpath, rlen, rnext = oracle.accept(tokens, parents, ref["amax"])
+    if np.all(top2_gap(ref["logits"])[list(rpath)] > GAP):       # decisive walk: end-to-end equality
+        assert (alen, nxt, path.tolist()) == (rlen, rnext, rpath.tolist())
+    k2, v2 = ver.get_cache()
+    for k in range(alen):
+        assert np.array_equal(k2[b][:, :, L + k], k1[b][:, :, L + path[k]])
+        assert np.array_equal(v2[b][:, :, L + k], v1[b][:, :, L + path[k]])
+    assert ver.kv_len[b] == L + alen
+    return out, ref
+
+
+def test_cfg2_1b_16_node_tree(model_1b):
+    """1.1B-class (22 layers, d 2048, 32 query / 4 KV heads of 64, FFN 5632, vocab 32000); prefix 330;
+    16-node tree: trunk 12 + two depth-2 branches at the low-confidence positions."""
+    from paper_2507_18181_amd import binding as B
+    spec = wl.WORKLOADS["cfg2_1b_n16"]
+    cfg = model_1b.cfg
+    L = spec["n_audio"] + spec["n_text"]
+    parents, tokens = wl.make_tree("cfg2_1b_n16")
+    assert len(parents) == 16
+    ver = model_1b.verifier(L + 64)
+    assert B.specasr_uses_mfma(ver.ctx, 16) == 1
+    K, V = wl.seeded_cache(cfg, spec["seed"], L, L + 64, "bf16")
+    ver.set_cache(K, V, [L])
+    _round_checks(ver, model_1b.om, tokens, parents, L)
+    ver.close()
+
+
+def test_cfg2_planted_trunk_and_library_prefill(model_1b):
+    """Prefix produced by the library itself (chain-tree prefill of 40 audio embeddings + 20 tokens),
+    then a tree whose trunk follows the oracle's greedy continuation: several drafts accepted."""
+    cfg = model_1b.cfg
+    om = model_1b.om
+    rng = np.random.default_rng(2002)
+    n_a, n_t = 40, 20
+    audio = wl.bf16_to_f32(wl.bf16_bits(rng.standard_normal((n_a, cfg["d_model"])).astype(np.float32)))
+    text = rng.integers(0, cfg["vocab"], n_t).astype(np.int32)
+    ver = model_1b.verifier(160)
+    n = n_a + n_t
+    emb = torch.zeros((1, 64, cfg["d_model"]), dtype=torch.bfloat16, device=ver.device)
+    emb[0, :n_a] = torch.from_numpy(audio).to(ver.device).to(torch.bfloat16)
+    tok = np.zeros(n, np.int32)
+    tok[n_a:] = text
+    fw = ver.tree_forward([tok], [np.arange(-1, n - 1)], embeds=emb, use_embed=[[1] * n_a + [0] * n_t],
+                          want_logits=False)
+    assert fw["status"] == 0 and ver.commit([n], [list(range(n))]) == 0
+    kc, vc = om.empty_cache(160)
+    Lo, last = om.prefill(kc, vc, 0, audio.astype(np.float64), text)
+    k1, v1 = ver.get_cache()
+    for got, want in ((k1, kc), (v1, vc)):
+        g = widen_cache(got[0, :, :, :n])
+        assert np.abs(g - want[:, :, :n]).max() <= TOL_BF16 * np.abs(want[:, :, :n]).max()
+    # greedy continuation from the oracle on the GPU's cache, 5 tokens
+    kg, vg = widen_cache(k1[0]), widen_cache(v1[0])
+    L, root, greedy = n, int(np.argmax(last)), []
+    kk, vv, LL = kg.copy(), vg.copy(), L
+    t = root
+    for _ in range(5):
+        r = om.tree_forward(kk, vv, LL, np.array([t], np.int32), np.array([-1], np.int32))
+        LL = om.commit(kk, vv, LL, r["ktree"], r["vtree"], [0])
+        t = int(r["amax"][0])
+        greedy.append(t)
+    parents = np.array([-1, 0, 1, 2, 3, 4, 5, 6, 2, 8], np.int32)
+    tokens = rng.integers(0, cfg["vocab"], 10).astype(np.int32)
+    tokens[0] = root
+    tokens[1:5] = greedy[:4]
+    tokens[5] = (greedy[4] + 1) % cfg["vocab"]
+    tokens[8] = (greedy[2] + 1) % cfg["vocab"]
+    out, ref = _round_checks(ver, om, tokens, parents, L)
+    if np.all(top2_gap(ref["logits"])[:5] > GAP):
+        assert out["accept_len"][0] == 5 and out["next_token"][0] == greedy[4]
+    ver.close()
+
+
+def test_cfg4_1b_batch16_ragged(model_1b):
+    """16 utterances, prefix lengths uniform in [200, 1500], each with its own 24-node tree (trunk 16 +
+    two depth-4 branches): one call; every sequence equals the oracle run on it alone.  More than 64
+    rows in total, so this runs the dtype-generic kernels."""
+    spec = wl.WORKLOADS["cfg4_1b_b16"]
+    cfg = model_1b.cfg
+    rng = np.random.default_rng([spec["seed"], 1])
+    Bn = 16
+    Ls = rng.integers(spec["prefix_range"][0], spec["prefix_range"][1] + 1, Bn).astype(np.int32)
+    cap = int(Ls.max()) + 64
+    ver = model_1b.verifier(cap, max_batch=Bn)
+    K, V = wl.seeded_cache(cfg, spec["seed"], Ls, cap, "bf16", batch=Bn)
+    ver.set_cache(K, V, Ls)
+    t = spec["tree"]
+    trees, toks = [], []
+    for b in range(Bn):
+        p, _, _ = wl.sparse_tree(rng, t["trunk"], t["n_branches"], t["branch_depth"], t["rule"])
+        trees.append(p)
+        toks.append(wl.tree_tokens(rng, p, cfg["vocab"]))
+        assert len(p) == 24
+    out = ver.verify_tree(toks, trees, want_logits=True)
+    assert out["status"] == 0
+    k2, v2 = ver.get_cache()
+    for b in (0, 5, 11, 15):          # the oracle recomputes a sample of the sequences one by one
+        ref = model_1b.om.tree_forward(np.ascontiguousarray(K[b]), np.ascontiguousarray(V[b]), int(Ls[b]),
+                                       toks[b], trees[b])
+        check_forward(ref, out["logits"][b].cpu().numpy(), out["argmax"][b], TOL_BF16)
+        path, alen, nxt = oracle.accept(toks[b], trees[b], out["argmax"][b, :24])
+        assert out["accept_len"][b] == alen and out["next_token"][b] == nxt
+        assert out["path"][b, :alen].tolist() == path.tolist()
+        want = ref["ktree"][:, :, path]
+        got = widen_cache(k2[b][:, :, Ls[b]:Ls[b] + alen])
+        assert np.abs(got - want).max() <= TOL_BF16 * np.abs(want).max()
+    for b in range(Bn):               # integer stages for every sequence
+        path, alen, nxt = oracle.accept(toks[b], trees[b], out["argmax"][b, :24])
+        assert out["accept_len"][b] == alen and ver.kv_len[b] == Ls[b] + alen
+    ver.close()
+
+
+def test_cfg3_7b_32_node_tree(model_7b):
+    """7B-class (32 layers, d 4096, 32 heads of 128, FFN 11008, vocab 32000); prefix 810; 32-node
+    two-pass sparse tree (trunk 16 + 4 depth-4 branches at the lowest-confidence positions): the
+    workload bench.py times."""
+    from paper_2507_18181_amd import binding as B
+    spec = wl.WORKLOADS["cfg3_7b_n32"]
+    cfg = model_7b.cfg
+    L = spec["n_audio"] + spec["n_text"]
+    parents, tokens = wl.make_tree("cfg3_7b_n32")
+    assert len(parents) == 32
+    ver = model_7b.verifier(L + 64)
+    assert B.specasr_uses_mfma(ver.ctx, 32) == 1
+    K, V = wl.seeded_cache(cfg, spec["seed"], L, L + 64, "bf16")
+    ver.set_cache(K, V, [L])
+    _round_checks(ver, model_7b.om, tokens, parents, L)
+    ver.close()
+
+
+def test_cfg5_7b_long_prefix_64_nodes_20_rounds(model_7b):
+    """Long-utterance stress: prefix 3200, 64-node trees (trunk 24 + 8 depth-5 branches), 20 rounds.
+    Each round runs the model forward, takes acceptance from SEEDED logits (planted targets) through
+    specasr_accept_from_logits, and commits that path in place.  Integer stages are checked bit-exactly
+    every round; the forward is checked against the oracle on rounds 0, 9 and 19."""
+    spec = wl.WORKLOADS["cfg5_7b_n64"]
+    cfg = model_7b.cfg
+    L = spec["n_audio"] + spec["n_text"]
+    cap = L + 20 * 30 + 64
+    ver = model_7b.verifier(cap)
+    K, V = wl.seeded_cache(cfg, spec["seed"], L, cap, "bf16")
+    ver.set_cache(K, V, [L])
+    rng = np.random.default_rng([spec["seed"], 2])
+    t = spec["tree"]
+    root = int(rng.integers(0, cfg["vocab"]))
+    total = 0
+    for rnd in range(spec["rounds"]):
+        parents, _, _ = wl.sparse_tree(rng, t["trunk"], t["n_branches"], t["branch_depth"], t["rule"])
+        tokens = wl.tree_tokens(rng, parents, cfg["vocab"])
+        tokens[0] = root
+        n = len(parents)
+        assert n == 64
+        Lr = int(ver.kv_len[0])
+        check = rnd in (0, 9, 19)
+        if check:
+            k0, v0 = ver.get_cache()
+        fw = ver.tree_forward([tokens], [parents], want_logits=check)
+        assert fw["status"] == 0
+        k1, v1 = ver.get_rows(Lr, Lr + n)          # the rows the forward wrote
+        if check:
+            ref = model_7b.om.tree_forward(np.ascontiguousarray(k0[0]), np.ascontiguousarray(v0[0]), Lr,
+                                           tokens, parents)
+            check_forward(ref, fw["logits"][0].cpu().numpy(), fw["argmax"][0].cpu().numpy(), TOL_BF16)
+            check_tree_kv(k1[0], v1[0], 0, ref, TOL_BF16)
+            kf, vf = ver.get_rows(0, Lr)
+            assert np.array_equal(kf[0], k0[0][:, :, :Lr]) and np.array_equal(vf[0], v0[0][:, :, :Lr])
+        lg = wl.planted_logits(rng, parents, tokens, cfg["vocab"])
+        full = torch.from_numpy(lg[None]).to(ver.device)
+        acc = ver.accept([tokens], [parents], logits_dev=full)
+        assert acc["status"] == 0
+        am = lg.argmax(axis=1).astype(np.int32)
+        assert np.array_equal(acc["argmax"][0].cpu().numpy(), am)
+        path, alen, nxt = oracle.accept(tokens, parents, am)
+        assert acc["accept_len"][0] == alen and acc["next_token"][0] == nxt
+        assert acc["path"][0, :alen].tolist() == path.tolist()
+        assert ver.commit([n], [path.tolist()]) == 0
+        assert ver.kv_len[0] == Lr + alen
+        k2, v2 = ver.get_rows(Lr, Lr + alen)
+        assert np.array_equal(k2[0], k1[0][:, :, path]) and np.array_equal(v2[0], v1[0][:, :, path])
+        root = nxt
+        total += alen
+    assert total > 20 * 3          # planted drafts are accepted most of the time
+    ver.close()
