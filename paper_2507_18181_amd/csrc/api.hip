@@ -95,7 +95,7 @@ inline int pad32(int v) { return (v + 31) / 32 * 32; }
 GemmPlan plan_gemm(int n_bands, int ksteps, int nb) {
   GemmPlan best;
   double best_cost = 1e300;
-  const int max_chunk = kGemmMaxLds / 1024 / nb;
+  const int max_chunk = kGemmMaxLds / 1024 / (2 * nb);  // hi and lo plane per node group
   for (int chunk = kGemmU; chunk <= max_chunk && chunk <= ksteps; chunk += kGemmU) {
     const int S = (ksteps + chunk - 1) / chunk;
     // spread the batches of kGemmU steps as evenly as possible over the S chunks
@@ -155,14 +155,14 @@ WsLayout ws_layout(const specasr_ctx *ctx, int batch) {
   const size_t dq = (size_t)c.n_heads * c.head_dim;
   size_t off = L.total;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-  L.hb = take(R * c.d_model * 2);
-  L.attb = take(R * dq * 2);
-  L.tb = take(R * c.d_ffn * 2);
+  L.hb = take(2 * R * c.d_model * 2);  // every bf16 activation buffer holds a hi and a lo plane
+  L.attb = take(2 * R * dq * 2);
+  L.tb = take(2 * R * c.d_ffn * 2);
   L.part = take((R < 64 ? R : 64) * ctx->part_floats * 4);
   const size_t nblk = (size_t)logits_argmax_blocks(c.vocab);
   L.blk_val = take(R * nblk * 4);
   L.blk_idx = take(R * nblk * 4);
-  L.qb = take(R * dq * 2);
+  L.qb = take(2 * R * dq * 2);
   const size_t mc = (size_t)tree_attention_max_chunks(c.n_kv_heads);
   L.attn_o = take(mc * R * dq * 4);
   L.attn_ml = take(mc * R * c.n_heads * 2 * 4);
@@ -370,14 +370,14 @@ specasr_status prof_drain(specasr_ctx *ctx) {
 
 // Launches one projection GEMM; brackets it with events when it is the profiled one.
 void gemm_stage(specasr_ctx *ctx, int stage, bool profiled_layer, const PackedMatrix &W,
-                const uint16_t *X, int ldx, int rows, float *part, const GemmPlan &plan,
-                hipStream_t st) {
+                const uint16_t *X, const uint16_t *Xlo, int ldx, int rows, float *part,
+                const GemmPlan &plan, hipStream_t st) {
   const bool prof = ctx->prof_stage == stage && profiled_layer && !ctx->prof_ev.empty();
   if (prof) {
     if (ctx->prof_used + 2 > ctx->prof_ev.size()) (void)prof_drain(ctx);
     (void)hipEventRecord(ctx->prof_ev[ctx->prof_used], st);
   }
-  launch_gemm_skinny(W, X, ldx, rows, part, plan, st);
+  launch_gemm_skinny(W, X, Xlo, ldx, rows, part, plan, st);
   if (prof) {
     (void)hipEventRecord(ctx->prof_ev[ctx->prof_used + 1], st);
     ctx->prof_used += 2;
@@ -397,8 +397,9 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
   float *x = (float *)(ws + L.x), *q = (float *)(ws + L.q), *att = (float *)(ws + L.att);
   float *part = (float *)(ws + L.part);
   uint16_t *hb = (uint16_t *)(ws + L.hb), *attb = (uint16_t *)(ws + L.attb), *tb = (uint16_t *)(ws + L.tb);
+  uint16_t *hb_lo = hb + (size_t)R * d, *attb_lo = attb + (size_t)R * dq, *tb_lo = tb + (size_t)R * F;
   float2 *cs = (float2 *)(ws + L.rope);
-  uint16_t *qb = (uint16_t *)(ws + L.qb);
+  uint16_t *qb = (uint16_t *)(ws + L.qb), *qb_lo = qb + (size_t)R * dq;
   const bool mfma_attn = tree_attention_supported(md.head_dim);
   const PackedLayer &p0 = ctx->packed[0];
   const GemmPlan pl_qkv = plan_gemm(p0.qkv.n_bands, p0.qkv.ksteps, nb);
@@ -423,27 +424,27 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
     const bool pl = l == prof_layer;
     const specasr_layer_weights &lw = ctx->layers[l];
     const PackedLayer &pk = ctx->packed[l];
-    launch_residual_norm(x, part, pending, R, pending_ld, lw.attn_norm, d, md.rms_eps, hb, st);
-    gemm_stage(ctx, SPECASR_STAGE_QKV, pl, pk.qkv, hb, d, R, part, pl_qkv, st);
+    launch_residual_norm(x, part, pending, R, pending_ld, lw.attn_norm, d, md.rms_eps, hb, hb_lo, st);
+    gemm_stage(ctx, SPECASR_STAGE_QKV, pl, pk.qkv, hb, hb_lo, d, R, part, pl_qkv, st);
     if (mfma_attn) {
-      launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, ctx->col_k, ctx->col_v, cs, nullptr, qb, kv->k, kv->v, st);
-      launch_tree_attention(m, md, g, l, hs.max_total_keys, hs.max_seq_nodes, qb, kv->k, kv->v,
-                            (float *)(ws + L.attn_o), (float *)(ws + L.attn_ml), attb, st);
+      launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, ctx->col_k, ctx->col_v, cs, nullptr, qb, qb_lo, kv->k, kv->v, st);
+      launch_tree_attention(m, md, g, l, hs.max_total_keys, hs.max_seq_nodes, qb, qb_lo, kv->k, kv->v,
+                            (float *)(ws + L.attn_o), (float *)(ws + L.attn_ml), attb, attb_lo, st);
     } else {
-      launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, ctx->col_k, ctx->col_v, cs, q, nullptr, kv->k, kv->v, st);
+      launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, ctx->col_k, ctx->col_v, cs, q, nullptr, nullptr, kv->k, kv->v, st);
       launch_attention_generic(m, md, g, l, q, kv->k, kv->v, att, st);
-      launch_to_bf16(att, (int64_t)R * dq, attb, st);
+      launch_to_bf16(att, (int64_t)R * dq, attb, attb_lo, st);
     }
-    gemm_stage(ctx, SPECASR_STAGE_O, pl, pk.o, attb, dq, R, part, pl_o, st);
-    launch_residual_norm(x, part, pl_o.n_splits, R, pk.o.ldo, lw.ffn_norm, d, md.rms_eps, hb, st);
-    gemm_stage(ctx, SPECASR_STAGE_GATE_UP, pl, pk.gu, hb, d, R, part, pl_gu, st);
-    launch_swiglu_finish(part, pl_gu.n_splits, R, pk.gu.ldo, ctx->col_up, F, tb, st);
-    gemm_stage(ctx, SPECASR_STAGE_DOWN, pl, pk.down, tb, F, R, part, pl_dn, st);
+    gemm_stage(ctx, SPECASR_STAGE_O, pl, pk.o, attb, attb_lo, dq, R, part, pl_o, st);
+    launch_residual_norm(x, part, pl_o.n_splits, R, pk.o.ldo, lw.ffn_norm, d, md.rms_eps, hb, hb_lo, st);
+    gemm_stage(ctx, SPECASR_STAGE_GATE_UP, pl, pk.gu, hb, hb_lo, d, R, part, pl_gu, st);
+    launch_swiglu_finish(part, pl_gu.n_splits, R, pk.gu.ldo, ctx->col_up, F, tb, tb_lo, st);
+    gemm_stage(ctx, SPECASR_STAGE_DOWN, pl, pk.down, tb, tb_lo, F, R, part, pl_dn, st);
     pending = pl_dn.n_splits;
     pending_ld = pk.down.ldo;
   }
-  launch_residual_norm(x, part, pending, R, pending_ld, ctx->w.final_norm, d, md.rms_eps, hb, st);
-  gemm_stage(ctx, SPECASR_STAGE_LM_HEAD, true, ctx->lm_head, hb, d, R, part, pl_lm, st);
+  launch_residual_norm(x, part, pending, R, pending_ld, ctx->w.final_norm, d, md.rms_eps, hb, hb_lo, st);
+  gemm_stage(ctx, SPECASR_STAGE_LM_HEAD, true, ctx->lm_head, hb, hb_lo, d, R, part, pl_lm, st);
   launch_logits_argmax(m, part, pl_lm.n_splits, ctx->lm_head.ldo, V, ctx->cfg.max_nodes, logits_dev,
                        (float *)(ws + L.blk_val), (int *)(ws + L.blk_idx), argmax_dev, st);
 }

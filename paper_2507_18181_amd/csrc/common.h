@@ -24,6 +24,12 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
   return (uint16_t)(u >> 16);
 }
 
+// v = hi + lo with both parts bf16: the pair carries 16 mantissa bits of v
+__device__ __forceinline__ void split_bf16(float v, uint16_t &hi, uint16_t &lo) {
+  hi = f32_to_bf16_bits(v);
+  lo = f32_to_bf16_bits(v - __uint_as_float(((uint32_t)hi) << 16));
+}
+
 template <class T> __device__ __forceinline__ T from_f32(float f);
 template <> __device__ __forceinline__ float from_f32<float>(float f) { return f; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float f) {

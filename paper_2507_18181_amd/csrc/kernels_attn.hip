@@ -9,6 +9,8 @@
 //   S^T[key][query] = K[key][:] . Q[query][:]      A = K tile (rows = keys, read straight from
 //                                                   the cache, 16 B per lane), B = Q^T
 //   online softmax per query column (fp32; max and sum via one cross-half shuffle)
+//   Q and P enter the matrix cores as hi + lo bf16 planes (two MFMAs), so only the bf16 storage
+//   of the cache itself limits the precision.
 //   O^T[c][query]  += V^T[c][key] * P^T[key][query] A = V^T gathered from an LDS copy of the V
 //                                                   tile with key pairs interleaved, B = P^T,
 //                                                   which is exactly how the lanes already hold P
@@ -32,6 +34,7 @@ template <int HD, int RGW>
 __global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g, int layer, int H,
                                                             int Hkv, int n_rgb,
                                                             const uint16_t *__restrict__ qb,
+                                                            const uint16_t *__restrict__ qb_lo,
                                                             const uint16_t *__restrict__ kc,
                                                             const uint16_t *__restrict__ vc,
                                                             int chunk_keys, float *__restrict__ o_part,
@@ -52,7 +55,7 @@ __global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g
   bool valid[RGW];
   int out_row[RGW], out_head[RGW];
   uint64_t anc[RGW];
-  u32x4 qreg[RGW][KK];
+  u32x4 qreg[RGW][KK], qlo[RGW][KK];  // queries as hi + lo bf16 planes
 #pragma unroll
   for (int w = 0; w < RGW; ++w) {
     const int qrow = (rgb * RGW + w) * 32 + ql;
@@ -61,10 +64,12 @@ __global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g
     out_row[w] = r0 + node;
     out_head[w] = kvh * G + gi;
     anc[w] = valid[w] ? m.anc[out_row[w]] : 0ull;
-    const uint16_t *qp = qb + ((int64_t)out_row[w] * H + out_head[w]) * HD + 8 * h;
+    const int64_t qoff = ((int64_t)out_row[w] * H + out_head[w]) * HD + 8 * h;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-      qreg[w][kk] = valid[w] ? *reinterpret_cast<const u32x4 *>(qp + 16 * kk) : (u32x4){0u, 0u, 0u, 0u};
+    for (int kk = 0; kk < KK; ++kk) {
+      qreg[w][kk] = valid[w] ? *reinterpret_cast<const u32x4 *>(qb + qoff + 16 * kk) : (u32x4){0u, 0u, 0u, 0u};
+      qlo[w][kk] = valid[w] ? *reinterpret_cast<const u32x4 *>(qb_lo + qoff + 16 * kk) : (u32x4){0u, 0u, 0u, 0u};
+    }
   }
   float m_run[RGW], l_run[RGW];
   f32x16 o[RGW][CB];
@@ -116,9 +121,12 @@ __global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g
 #pragma unroll
       for (int j = 0; j < 16; ++j) sT[j] = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
+      for (int kk = 0; kk < KK; ++kk) {
         sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[kk]),
                                                      __builtin_bit_cast(bf16x8, qreg[w][kk]), sT, 0, 0, 0);
+        sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[kk]),
+                                                     __builtin_bit_cast(bf16x8, qlo[w][kk]), sT, 0, 0, 0);
+      }
       // lane holds, for query ql, the keys t0 + 8*(j/4) + 4*h + j%4
       float mx = -INFINITY;
 #pragma unroll
@@ -149,9 +157,15 @@ __global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g
       // i = 0..7 are keys 16*mm + 8*(i/4) + 4*h + i%4, i.e. its own p[8*mm + i]
 #pragma unroll
       for (int mm = 0; mm < 2; ++mm) {
-        u32x4 pb;
+        u32x4 pb, pl;  // probabilities as hi + lo bf16 planes
 #pragma unroll
-        for (int i2 = 0; i2 < 4; ++i2) pb[i2] = pack_bf16(p[8 * mm + 2 * i2], p[8 * mm + 2 * i2 + 1]);
+        for (int i2 = 0; i2 < 4; ++i2) {
+          uint16_t h0, l0, h1, l1;
+          split_bf16(p[8 * mm + 2 * i2], h0, l0);
+          split_bf16(p[8 * mm + 2 * i2 + 1], h1, l1);
+          pb[i2] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+          pl[i2] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+        }
         // matching V^T k-slots: key pairs 8*mm + 2*h, +1, 8*mm + 4 + 2*h, +1
         const uint32_t *vrow = vp + (8 * mm + 2 * h) * HD + ql;
 #pragma unroll
@@ -163,6 +177,8 @@ __global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g
           va[3] = vrow[32 * cb + 5 * HD];
           o[w][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va),
                                                              __builtin_bit_cast(bf16x8, pb), o[w][cb], 0, 0, 0);
+          o[w][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va),
+                                                             __builtin_bit_cast(bf16x8, pl), o[w][cb], 0, 0, 0);
         }
       }
     }
@@ -192,7 +208,7 @@ __global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g
 __global__ void tree_attention_merge_kernel(StepMeta m, int H, int HD, int chunk_keys,
                                             const float *__restrict__ o_part,
                                             const float *__restrict__ ml_part,
-                                            uint16_t *__restrict__ out) {
+                                            uint16_t *__restrict__ out, uint16_t *__restrict__ out_lo) {
   const int a = blockIdx.x, r = blockIdx.y, c = threadIdx.x, rows = m.rows;
   const int seq = m.seq[r];
   const int T = m.kv_len[seq] + m.n_nodes[seq];
@@ -207,26 +223,27 @@ __global__ void tree_attention_merge_kernel(StepMeta m, int H, int HD, int chunk
     num += wgt * o_part[base * HD + c];
     den += wgt * ml_part[base * 2 + 1];
   }
-  out[((int64_t)r * H + a) * HD + c] = f32_to_bf16_bits(num / den);
+  const int64_t oi = ((int64_t)r * H + a) * HD + c;
+  split_bf16(num / den, out[oi], out_lo[oi]);
 }
 
 template <int HD>
 static void launch_attn_hd(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
                            int max_seq_nodes, int chunk_keys, int n_chunks, const uint16_t *qb,
-                           const void *kc, const void *vc, float *o_part, float *ml_part,
-                           uint16_t *out, hipStream_t st) {
+                           const uint16_t *qb_lo, const void *kc, const void *vc, float *o_part,
+                           float *ml_part, uint16_t *out, uint16_t *out_lo, hipStream_t st) {
   const int G = md.n_heads / md.n_kv_heads;
   const int row_groups = (G * max_seq_nodes + 31) / 32;
   if (row_groups <= 1) {
     dim3 grid(n_chunks, md.n_kv_heads, m.batch);
-    tree_attention_kernel<HD, 1><<<grid, 64, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, 1, qb, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, o_part, ml_part);
+    tree_attention_kernel<HD, 1><<<grid, 64, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, 1, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, o_part, ml_part);
   } else {
     const int n_rgb = (row_groups + 1) / 2;
     dim3 grid(n_chunks, md.n_kv_heads * n_rgb, m.batch);
-    tree_attention_kernel<HD, 2><<<grid, 64, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, n_rgb, qb, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, o_part, ml_part);
+    tree_attention_kernel<HD, 2><<<grid, 64, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, n_rgb, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, o_part, ml_part);
   }
   dim3 mgrid(md.n_heads, m.rows);
-  tree_attention_merge_kernel<<<mgrid, HD, 0, st>>>(m, md.n_heads, HD, chunk_keys, o_part, ml_part, out);
+  tree_attention_merge_kernel<<<mgrid, HD, 0, st>>>(m, md.n_heads, HD, chunk_keys, o_part, ml_part, out, out_lo);
 }
 
 bool tree_attention_supported(int head_dim) { return head_dim == 64 || head_dim == 128; }
@@ -243,17 +260,17 @@ int tree_attention_chunk_keys(int max_total_keys, int n_kv_heads, int batch, int
 
 void launch_tree_attention(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
                            int max_total_keys, int max_seq_nodes, const uint16_t *qb,
-                           const void *kc, const void *vc, float *o_part, float *ml_part,
-                           uint16_t *out, hipStream_t st) {
+                           const uint16_t *qb_lo, const void *kc, const void *vc, float *o_part,
+                           float *ml_part, uint16_t *out, uint16_t *out_lo, hipStream_t st) {
   const int G = md.n_heads / md.n_kv_heads;
   const int row_groups = (G * max_seq_nodes + 31) / 32;
   const int n_rgb = row_groups <= 1 ? 1 : (row_groups + 1) / 2;
   const int ck = tree_attention_chunk_keys(max_total_keys, md.n_kv_heads, m.batch, n_rgb);
   const int n_chunks = (max_total_keys + ck - 1) / ck;
   if (md.head_dim == 64)
-    launch_attn_hd<64>(m, md, g, layer, max_seq_nodes, ck, n_chunks, qb, kc, vc, o_part, ml_part, out, st);
+    launch_attn_hd<64>(m, md, g, layer, max_seq_nodes, ck, n_chunks, qb, qb_lo, kc, vc, o_part, ml_part, out, out_lo, st);
   else
-    launch_attn_hd<128>(m, md, g, layer, max_seq_nodes, ck, n_chunks, qb, kc, vc, o_part, ml_part, out, st);
+    launch_attn_hd<128>(m, md, g, layer, max_seq_nodes, ck, n_chunks, qb, qb_lo, kc, vc, o_part, ml_part, out, out_lo, st);
 }
 
 }  // namespace specasr

@@ -25,17 +25,18 @@ struct GemmPlan {
 void launch_repack(const void *src, int n_out, int K, int ksteps_pad, void *dst, int band0,
                    hipStream_t st);
 hipError_t gemm_skinny_set_lds_limit();
-void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *X, int ldx, int rows, float *part,
-                        const GemmPlan &plan, hipStream_t st);
+void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *X, const uint16_t *Xlo, int ldx,
+                        int rows, float *part, const GemmPlan &plan, hipStream_t st);
 void launch_residual_norm(float *x, const float *part, int n_splits, int rows, int ldp,
-                          const void *gain, int d, float eps, uint16_t *hb, hipStream_t st);
+                          const void *gain, int d, float eps, uint16_t *hb, uint16_t *hb_lo,
+                          hipStream_t st);
 void launch_qkv_finish(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
                        const float *part, int n_splits, int ldp, int col_k, int col_v,
-                       const float2 *cs, float *q, uint16_t *qb, void *kc, void *vc,
+                       const float2 *cs, float *q, uint16_t *qb, uint16_t *qb_lo, void *kc, void *vc,
                        hipStream_t st);
 void launch_swiglu_finish(const float *part, int n_splits, int rows, int ldp, int col_up, int F,
-                          uint16_t *t, hipStream_t st);
-void launch_to_bf16(const float *src, int64_t n, uint16_t *dst, hipStream_t st);
+                          uint16_t *t, uint16_t *t_lo, hipStream_t st);
+void launch_to_bf16(const float *src, int64_t n, uint16_t *dst, uint16_t *dst_lo, hipStream_t st);
 int logits_argmax_blocks(int V);
 void launch_logits_argmax(const StepMeta &m, const float *part, int n_splits, int ldp, int V,
                           int max_nodes, float *logits_out, float *blk_val, int *blk_idx,
@@ -46,7 +47,7 @@ bool tree_attention_supported(int head_dim);
 int tree_attention_max_chunks(int n_kv_heads);
 void launch_tree_attention(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
                            int max_total_keys, int max_seq_nodes, const uint16_t *qb,
-                           const void *kc, const void *vc, float *o_part, float *ml_part,
-                           uint16_t *out, hipStream_t st);
+                           const uint16_t *qb_lo, const void *kc, const void *vc, float *o_part,
+                           float *ml_part, uint16_t *out, uint16_t *out_lo, hipStream_t st);
 
 }  // namespace specasr

@@ -11,6 +11,10 @@
 //     shuffle and no LDS round trip.
 //   * The activations (the B operand, <= 64 rows) are tiny: the workgroup stages its k-chunk of
 //     them into LDS once, already in B-operand order, and every wavefront re-reads them from there.
+//     They are carried as TWO bf16 planes, hi = bf16(v) and lo = bf16(v - hi), and every weight
+//     tile is multiplied with both: the products are exact in fp32, so the projections see the
+//     activations to 16 mantissa bits.  The matrix cores have >10x headroom on this stage; the
+//     extra MFMA is what keeps 22-32 layers inside the 2e-2 logit tolerance.
 //   * Work is split over (k-chunk, band group) so that a few thousand wavefronts each stream a
 //     contiguous span with a ring of loads in flight; partial sums over the k-chunks are written
 //     to a small fp32 buffer and reduced, in a fixed order, by the consumer stage.
@@ -52,13 +56,14 @@ void launch_repack(const void *src, int n_out, int K, int ksteps_pad, void *dst,
 // --------------------------------------------------------------------------- skinny GEMM
 // part[s][row][o] = sum over k in chunk s of X[row][k] * W[o][k]
 // grid.x = n_splits * n_groups; block = 256 (4 wavefronts); wavefront w of group g owns bands
-// [(g*4+w)*bpw, +bpw).  LDS: X chunk in B-operand order, [kstep][NB][64 lanes] x 16 bytes.
+// [(g*4+w)*bpw, +bpw).  LDS: X chunk in B-operand order, [kstep][NB][hi|lo][64 lanes] x 16 bytes.
 // Every chunk holds a whole number of U-tile batches (the packed k extent is padded to that), so
 // the steady-state loop is branch-free: U unconditional loads stay in flight per lane, the ring
 // runs on across band boundaries, and at the very end it re-reads the last batch (unused).
 template <int NB, int U>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4 *__restrict__ Wp,
-                                                          const uint16_t *__restrict__ X, int ldx,
+                                                          const uint16_t *__restrict__ X,
+                                                          const uint16_t *__restrict__ Xlo, int ldx,
                                                           int K, float *__restrict__ part, int ldo,
                                                           int rows, int n_bands, int ksteps_all,
                                                           int n_splits, int chunk_steps, int bpw) {
@@ -79,19 +84,19 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4 *__restric
     for (int u = 0; u < U; ++u) buf[u] = load_stream(p + 64 * u);
   }
   // stage the activation chunk: slot (kstep, nb, l) <- X[nb*32 + l%32][16*(ks0+kstep) + 8*(l/32) ..+7]
-  for (int idx = threadIdx.x; idx < nks * NB * 64; idx += 256) {
+  for (int idx = threadIdx.x; idx < nks * NB * 128; idx += 256) {
     const int l = idx & 63, blk = idx >> 6;
-    const int nb = blk % NB, kstep = blk / NB;
+    const int part_lo = blk & 1, nb = (blk >> 1) % NB, kstep = (blk >> 1) / NB;
     const int r = nb * 32 + (l & 31);
     const int col = 16 * (ks0 + kstep) + 8 * (l >> 5);
     u32x4 v = (u32x4){0u, 0u, 0u, 0u};
-    if (r < rows && col < K) v = *reinterpret_cast<const u32x4 *>(X + (int64_t)r * ldx + col);
+    if (r < rows && col < K) v = *reinterpret_cast<const u32x4 *>((part_lo ? Xlo : X) + (int64_t)r * ldx + col);
     lds[idx] = v;
   }
   __syncthreads();
 
   for (int band = b0; band < b1; ++band) {
-    // two accumulator sets per node group: consecutive tiles do not wait on each other
+    // two accumulator sets per node group (hi and lo plane): independent MFMA chains
     f32x16 acc[NB][2];
 #pragma unroll
     for (int n = 0; n < NB; ++n)
@@ -110,8 +115,10 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4 *__restric
         const bf16x8 a = __builtin_bit_cast(bf16x8, buf[u]);
 #pragma unroll
         for (int n = 0; n < NB; ++n) {
-          const bf16x8 b = __builtin_bit_cast(bf16x8, lds[((kb + u) * NB + n) * 64 + lane]);
-          acc[n][u & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[n][u & 1], 0, 0, 0);
+          const bf16x8 bh = __builtin_bit_cast(bf16x8, lds[(((kb + u) * NB + n) * 2) * 64 + lane]);
+          const bf16x8 bl = __builtin_bit_cast(bf16x8, lds[(((kb + u) * NB + n) * 2 + 1) * 64 + lane]);
+          acc[n][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bh, acc[n][0], 0, 0, 0);
+          acc[n][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bl, acc[n][1], 0, 0, 0);
         }
         buf[u] = load_stream(pn + 64 * u);  // refill the slot just consumed
       }
@@ -132,16 +139,16 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4 *__restric
   }
 }
 
-void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *X, int ldx, int rows, float *part,
-                        const GemmPlan &plan, hipStream_t st) {
+void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *X, const uint16_t *Xlo, int ldx,
+                        int rows, float *part, const GemmPlan &plan, hipStream_t st) {
   const int groups = (W.n_bands + 4 * plan.bands_per_wave - 1) / (4 * plan.bands_per_wave);
   const dim3 grid(groups * plan.n_splits);
   const int nb = rows <= 32 ? 1 : 2;
-  const size_t lds = (size_t)plan.chunk_steps * nb * 64 * 16;
+  const size_t lds = (size_t)plan.chunk_steps * nb * 2 * 64 * 16;
   if (nb == 1)
-    gemm_skinny_kernel<1, kGemmU><<<grid, 256, lds, st>>>((const u32x4 *)W.data, X, ldx, W.k_real, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits, plan.chunk_steps, plan.bands_per_wave);
+    gemm_skinny_kernel<1, kGemmU><<<grid, 256, lds, st>>>((const u32x4 *)W.data, X, Xlo, ldx, W.k_real, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits, plan.chunk_steps, plan.bands_per_wave);
   else
-    gemm_skinny_kernel<2, kGemmU><<<grid, 256, lds, st>>>((const u32x4 *)W.data, X, ldx, W.k_real, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits, plan.chunk_steps, plan.bands_per_wave);
+    gemm_skinny_kernel<2, kGemmU><<<grid, 256, lds, st>>>((const u32x4 *)W.data, X, Xlo, ldx, W.k_real, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits, plan.chunk_steps, plan.bands_per_wave);
 }
 
 hipError_t gemm_skinny_set_lds_limit() {
@@ -155,7 +162,8 @@ hipError_t gemm_skinny_set_lds_limit() {
 // hb[r][:]  = bf16( x[r][:] * rsqrt(mean(x^2) + eps) * gain )
 __global__ __launch_bounds__(1024) void residual_norm_kernel(float *x, const float *part, int n_splits,
                                                              int rows, int ldp, const uint16_t *gain,
-                                                             int d, float eps, uint16_t *hb) {
+                                                             int d, float eps, uint16_t *hb,
+                                                             uint16_t *hb_lo) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   float *xr = x + (int64_t)r * d;
@@ -187,18 +195,22 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(float *x, const flo
   for (int c = threadIdx.x * 4; c < d; c += 4096) {
     const float4 v = *reinterpret_cast<const float4 *>(xr + c);
     const uint2 g = *reinterpret_cast<const uint2 *>(gain + c);
-    uint2 o;
-    o.x = (uint32_t)f32_to_bf16_bits(v.x * rs * bf16_bits_to_f32(g.x & 0xffffu)) |
-          ((uint32_t)f32_to_bf16_bits(v.y * rs * bf16_bits_to_f32(g.x >> 16)) << 16);
-    o.y = (uint32_t)f32_to_bf16_bits(v.z * rs * bf16_bits_to_f32(g.y & 0xffffu)) |
-          ((uint32_t)f32_to_bf16_bits(v.w * rs * bf16_bits_to_f32(g.y >> 16)) << 16);
-    *reinterpret_cast<uint2 *>(hb + (int64_t)r * d + c) = o;
+    const float y[4] = {v.x * rs * bf16_bits_to_f32(g.x & 0xffffu), v.y * rs * bf16_bits_to_f32(g.x >> 16),
+                        v.z * rs * bf16_bits_to_f32(g.y & 0xffffu), v.w * rs * bf16_bits_to_f32(g.y >> 16)};
+    uint16_t hi[4], lo[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) split_bf16(y[i], hi[i], lo[i]);
+    *reinterpret_cast<uint2 *>(hb + (int64_t)r * d + c) =
+        make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+    *reinterpret_cast<uint2 *>(hb_lo + (int64_t)r * d + c) =
+        make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
   }
 }
 
 void launch_residual_norm(float *x, const float *part, int n_splits, int rows, int ldp,
-                          const void *gain, int d, float eps, uint16_t *hb, hipStream_t st) {
-  residual_norm_kernel<<<rows, 1024, 0, st>>>(x, part, n_splits, rows, ldp, (const uint16_t *)gain, d, eps, hb);
+                          const void *gain, int d, float eps, uint16_t *hb, uint16_t *hb_lo,
+                          hipStream_t st) {
+  residual_norm_kernel<<<rows, 1024, 0, st>>>(x, part, n_splits, rows, ldp, (const uint16_t *)gain, d, eps, hb, hb_lo);
 }
 
 // q, k, v = sum of partials; rotary embedding at the node's depth position (Sec. II-B: each
@@ -209,7 +221,8 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(StepMeta m, KvGeom g, i
                                                          int hd, const float *part, int n_splits,
                                                          int ldp, int col_k, int col_v,
                                                          const float2 *cs, float *q, uint16_t *qb,
-                                                         float qscale, uint16_t *kc, uint16_t *vc) {
+                                                         uint16_t *qb_lo, float qscale, uint16_t *kc,
+                                                         uint16_t *vc) {
   const int r = blockIdx.y, half = hd / 2, rows = m.rows;
   const int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= (H + Hkv) * half) return;
@@ -227,8 +240,8 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(StepMeta m, KvGeom g, i
     const float y0 = x0 * c.x - x1 * c.y, y1 = x1 * c.x + x0 * c.y;
     const int64_t o = ((int64_t)r * H + a) * hd + j;
     if (qb) {
-      qb[o] = f32_to_bf16_bits(y0 * qscale);
-      qb[o + half] = f32_to_bf16_bits(y1 * qscale);
+      split_bf16(y0 * qscale, qb[o], qb_lo[o]);
+      split_bf16(y1 * qscale, qb[o + half], qb_lo[o + half]);
     } else {
       q[o] = y0;
       q[o + half] = y1;
@@ -246,16 +259,17 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(StepMeta m, KvGeom g, i
 
 void launch_qkv_finish(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
                        const float *part, int n_splits, int ldp, int col_k, int col_v,
-                       const float2 *cs, float *q, uint16_t *qb, void *kc, void *vc,
+                       const float2 *cs, float *q, uint16_t *qb, uint16_t *qb_lo, void *kc, void *vc,
                        hipStream_t st) {
   const int items = (md.n_heads + md.n_kv_heads) * (md.head_dim / 2);
   dim3 grid((items + 255) / 256, m.rows);
-  qkv_finish_kernel<<<grid, 256, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, md.head_dim, part, n_splits, ldp, col_k, col_v, cs, q, qb, 1.0f / sqrtf((float)md.head_dim), (uint16_t *)kc, (uint16_t *)vc);
+  qkv_finish_kernel<<<grid, 256, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, md.head_dim, part, n_splits, ldp, col_k, col_v, cs, q, qb, qb_lo, 1.0f / sqrtf((float)md.head_dim), (uint16_t *)kc, (uint16_t *)vc);
 }
 
 // t[r][f] = bf16( silu(sum_s gate) * (sum_s up) ); gate at column f, up at column col_up + f
 __global__ __launch_bounds__(256) void swiglu_finish_kernel(const float *part, int n_splits, int rows,
-                                                            int ldp, int col_up, int F, uint16_t *t) {
+                                                            int ldp, int col_up, int F, uint16_t *t,
+                                                            uint16_t *t_lo) {
   const int r = blockIdx.y;
   const int f = (blockIdx.x * 256 + threadIdx.x) * 4;
   if (f >= F) return;
@@ -268,31 +282,39 @@ __global__ __launch_bounds__(256) void swiglu_finish_kernel(const float *part, i
     up.x += b.x; up.y += b.y; up.z += b.z; up.w += b.w;
   }
   auto act = [](float gv, float uv) { return gv / (1.0f + __expf(-gv)) * uv; };
-  uint2 o;
-  o.x = (uint32_t)f32_to_bf16_bits(act(gt.x, up.x)) | ((uint32_t)f32_to_bf16_bits(act(gt.y, up.y)) << 16);
-  o.y = (uint32_t)f32_to_bf16_bits(act(gt.z, up.z)) | ((uint32_t)f32_to_bf16_bits(act(gt.w, up.w)) << 16);
-  *reinterpret_cast<uint2 *>(t + (int64_t)r * F + f) = o;
+  const float y[4] = {act(gt.x, up.x), act(gt.y, up.y), act(gt.z, up.z), act(gt.w, up.w)};
+  uint16_t hi[4], lo[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) split_bf16(y[i], hi[i], lo[i]);
+  *reinterpret_cast<uint2 *>(t + (int64_t)r * F + f) =
+      make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+  *reinterpret_cast<uint2 *>(t_lo + (int64_t)r * F + f) =
+      make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
 }
 
 void launch_swiglu_finish(const float *part, int n_splits, int rows, int ldp, int col_up, int F,
-                          uint16_t *t, hipStream_t st) {
+                          uint16_t *t, uint16_t *t_lo, hipStream_t st) {
   dim3 grid((F / 4 + 255) / 256, rows);
-  swiglu_finish_kernel<<<grid, 256, 0, st>>>(part, n_splits, rows, ldp, col_up, F, t);
+  swiglu_finish_kernel<<<grid, 256, 0, st>>>(part, n_splits, rows, ldp, col_up, F, t, t_lo);
 }
 
 // fp32 -> bf16 row conversion (attention output feeding the output projection)
-__global__ void to_bf16_kernel(const float *src, int64_t n, uint16_t *dst) {
+__global__ void to_bf16_kernel(const float *src, int64_t n, uint16_t *dst, uint16_t *dst_lo) {
   int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (i >= n) return;
   const float4 v = *reinterpret_cast<const float4 *>(src + i);
-  uint2 o;
-  o.x = (uint32_t)f32_to_bf16_bits(v.x) | ((uint32_t)f32_to_bf16_bits(v.y) << 16);
-  o.y = (uint32_t)f32_to_bf16_bits(v.z) | ((uint32_t)f32_to_bf16_bits(v.w) << 16);
-  *reinterpret_cast<uint2 *>(dst + i) = o;
+  const float y[4] = {v.x, v.y, v.z, v.w};
+  uint16_t hi[4], lo[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) split_bf16(y[k], hi[k], lo[k]);
+  *reinterpret_cast<uint2 *>(dst + i) =
+      make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+  *reinterpret_cast<uint2 *>(dst_lo + i) =
+      make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
 }
 
-void launch_to_bf16(const float *src, int64_t n, uint16_t *dst, hipStream_t st) {
-  to_bf16_kernel<<<(unsigned)((n / 4 + 255) / 256), 256, 0, st>>>(src, n, dst);
+void launch_to_bf16(const float *src, int64_t n, uint16_t *dst, uint16_t *dst_lo, hipStream_t st) {
+  to_bf16_kernel<<<(unsigned)((n / 4 + 255) / 256), 256, 0, st>>>(src, n, dst, dst_lo);
 }
 
 // logits[r][v] = sum_s part[s][r][v]; per-(row, block) best (value, lowest index); optional

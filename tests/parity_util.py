@@ -33,6 +33,7 @@ def check_forward(ref, gpu_logits, gpu_argmax, tol):
     Returns the decisive mask."""
     n = ref["logits"].shape[0]
     err = row_rel_err(gpu_logits[:n], ref["logits"])
+    print("logit rel err: max %.3e mean %.3e (tol %g, %d rows)" % (err.max(), err.mean(), tol, n))
     assert err.max() <= tol, "logit rel err %s > %g" % (err, tol)
     dec = top2_gap(ref["logits"]) > GAP
     assert np.array_equal(np.asarray(gpu_argmax[:n])[dec], ref["amax"][dec])
