@@ -106,8 +106,8 @@ GemmPlan plan_gemm(int n_bands, int ksteps, int nb) {
       const int groups = (n_bands + 4 * bpw - 1) / (4 * bpw);
       const long wgs = (long)groups * S;
       const long rounds = (wgs + 255) / 256;
-      const double stream = (double)rounds * ((double)bpw * chunk + 8.0);
-      const double partial = (double)S * 32.0 * nb * n_bands * 32.0 * 4.0 / 1024.0 * 0.5 / 1024.0;
+      const double stream = (double)rounds * ((double)bpw * chunk + 4.0);
+      const double partial = (double)S * 32.0 * nb * n_bands * 32.0 * 4.0 / 1024.0 * 1.0 / 1024.0;
       const double cost = stream + partial;
       if (cost < best_cost) {
         best_cost = cost;

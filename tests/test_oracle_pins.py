@@ -458,3 +458,20 @@ def test_argmax_takes_lowest_index_on_exact_ties():
         r = oracle.OracleModel(cfg, w2).tree_forward(kc, vc, 0, tok, par)
         assert r["logits"][0, u] == r["logits"][0, t]
         assert r["amax"][0] == min(t, u)
+
+
+def test_oracle_regression_against_stored_results():
+    """The oracle still produces what tests/golden/make_golden.py (oracle-only script) stored."""
+    import json
+    import os
+    import importlib.util
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "golden", "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    got = mod.compute()
+    want = json.load(open(os.path.join(here, "golden", "cfg1_oracle.json")))
+    for k in ("kv_len", "tokens", "parents", "amax", "path", "accept_len", "next_token"):
+        assert got[k] == want[k], k
+    for k in ("logits_node0_first8", "logits_node7_first8"):
+        assert np.allclose(got[k], want[k], rtol=1e-9, atol=1e-12)
