@@ -66,6 +66,7 @@ struct specasr_ctx {
   size_t out_host_words = 0;
   int32_t last_hip = 0;
   int device = 0;
+  int n_cu = 256;  // compute units = workgroups of the persistent-style GEMM grid
   bool staging_ready = false;
 };
 
@@ -88,33 +89,26 @@ size_t meta_words(int rows_max, int batch) {
 
 inline int pad32(int v) { return (v + 31) / 32 * 32; }
 
-// Chooses the k-split and the bands per wavefront of one skinny GEMM.  Fitted to a sweep on
-// MI355X: the stage is HBM bound and runs best as about one workgroup per compute unit, each
-// wavefront streaming as long a contiguous span as possible; the model charges rounds of 256
-// workgroups, a fixed start-up per wavefront, and the partial-sum traffic of the k-split.
-GemmPlan plan_gemm(int n_bands, int ksteps, int nb) {
+// Chooses the k-split S of one skinny GEMM (workgroup g takes chunk g % S and every (P/S)-th
+// band).  Cost model fitted to measurements on MI355X, in microseconds per wavefront: 0.33 per
+// weight tile streamed, 0.45 per band (cross-wavefront reduction and partial write), 0.34 per
+// k-step of activations loaded into registers.  The slice of a wavefront must fit its ring.
+GemmPlan plan_gemm(int n_bands, int ksteps, int nb, int n_cu) {
   GemmPlan best;
   double best_cost = 1e300;
-  const int max_chunk = kGemmMaxLds / 1024 / (2 * nb);  // hi and lo plane per node group
-  for (int chunk = kGemmU; chunk <= max_chunk && chunk <= ksteps; chunk += kGemmU) {
-    const int S = (ksteps + chunk - 1) / chunk;
-    // spread the batches of kGemmU steps as evenly as possible over the S chunks
-    const int batches = ksteps / kGemmU;
-    const int chunk_bal = ((batches + S - 1) / S) * kGemmU;
-    if (chunk_bal != chunk || (S - 1) * chunk_bal >= ksteps) continue;
-    for (int bpw = 1; bpw <= 64; ++bpw) {
-      const int groups = (n_bands + 4 * bpw - 1) / (4 * bpw);
-      const long wgs = (long)groups * S;
-      const long rounds = (wgs + 255) / 256;
-      const double stream = (double)rounds * ((double)bpw * chunk + 4.0);
-      const double partial = (double)S * 32.0 * nb * n_bands * 32.0 * 4.0 / 1024.0 * 1.0 / 1024.0;
-      const double cost = stream + partial;
-      if (cost < best_cost) {
-        best_cost = cost;
-        best.n_splits = S;
-        best.chunk_steps = chunk;
-        best.bands_per_wave = bpw;
-      }
+  const int lw_max = nb == 1 ? 16 : 8;
+  for (int S = 1; S <= 64; S *= 2) {
+    if (n_cu % S) break;
+    const int chunk = (ksteps + S - 1) / S;
+    const int len = (chunk + 7) / 8;  // k-steps of the longest wavefront slice
+    if (len > lw_max) continue;
+    const int units = (n_bands + n_cu / S - 1) / (n_cu / S);
+    const double cost = 0.33 * units * len + 0.45 * units + 0.34 * nb * len;
+    if (cost < best_cost) {
+      best_cost = cost;
+      best.n_splits = S;
+      best.lw = nb == 1 ? (len <= 4 ? 4 : len <= 8 ? 8 : len <= 12 ? 12 : 16) : (len <= 4 ? 4 : 8);
+      best.grid = n_cu;
     }
   }
   return best;
@@ -155,9 +149,10 @@ WsLayout ws_layout(const specasr_ctx *ctx, int batch) {
   const size_t dq = (size_t)c.n_heads * c.head_dim;
   size_t off = L.total;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-  L.hb = take(2 * R * c.d_model * 2);  // every bf16 activation buffer holds a hi and a lo plane
-  L.attb = take(2 * R * dq * 2);
-  L.tb = take(2 * R * c.d_ffn * 2);
+  // packed activation buffers: hi and lo plane, each [k/16][node groups][64 lanes][8] for <= 64 rows
+  L.hb = take(2 * 64 * (size_t)c.d_model * 2);
+  L.attb = take(2 * 64 * dq * 2);
+  L.tb = take(2 * 64 * (size_t)c.d_ffn * 2);
   L.part = take((R < 64 ? R : 64) * ctx->part_floats * 4);
   const size_t nblk = (size_t)logits_argmax_blocks(c.vocab);
   L.blk_val = take(R * nblk * 4);
@@ -370,14 +365,13 @@ specasr_status prof_drain(specasr_ctx *ctx) {
 
 // Launches one projection GEMM; brackets it with events when it is the profiled one.
 void gemm_stage(specasr_ctx *ctx, int stage, bool profiled_layer, const PackedMatrix &W,
-                const uint16_t *X, const uint16_t *Xlo, int ldx, int rows, float *part,
-                const GemmPlan &plan, hipStream_t st) {
+                const uint16_t *Xp, int rows, float *part, const GemmPlan &plan, hipStream_t st) {
   const bool prof = ctx->prof_stage == stage && profiled_layer && !ctx->prof_ev.empty();
   if (prof) {
     if (ctx->prof_used + 2 > ctx->prof_ev.size()) (void)prof_drain(ctx);
     (void)hipEventRecord(ctx->prof_ev[ctx->prof_used], st);
   }
-  launch_gemm_skinny(W, X, Xlo, ldx, rows, part, plan, st);
+  launch_gemm_skinny(W, Xp, rows, part, plan, st);
   if (prof) {
     (void)hipEventRecord(ctx->prof_ev[ctx->prof_used + 1], st);
     ctx->prof_used += 2;
@@ -397,24 +391,25 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
   float *x = (float *)(ws + L.x), *q = (float *)(ws + L.q), *att = (float *)(ws + L.att);
   float *part = (float *)(ws + L.part);
   uint16_t *hb = (uint16_t *)(ws + L.hb), *attb = (uint16_t *)(ws + L.attb), *tb = (uint16_t *)(ws + L.tb);
-  uint16_t *hb_lo = hb + (size_t)R * d, *attb_lo = attb + (size_t)R * dq, *tb_lo = tb + (size_t)R * F;
+  // lo planes follow the hi planes: one plane holds k * 32 * nb elements
+  uint16_t *hb_lo = hb + (size_t)d * 32 * nb, *attb_lo = attb + (size_t)dq * 32 * nb, *tb_lo = tb + (size_t)F * 32 * nb;
   float2 *cs = (float2 *)(ws + L.rope);
   uint16_t *qb = (uint16_t *)(ws + L.qb), *qb_lo = qb + (size_t)R * dq;
   const bool mfma_attn = tree_attention_supported(md.head_dim);
   const PackedLayer &p0 = ctx->packed[0];
-  const GemmPlan pl_qkv = plan_gemm(p0.qkv.n_bands, p0.qkv.ksteps, nb);
-  const GemmPlan pl_o = plan_gemm(p0.o.n_bands, p0.o.ksteps, nb);
-  const GemmPlan pl_gu = plan_gemm(p0.gu.n_bands, p0.gu.ksteps, nb);
-  const GemmPlan pl_dn = plan_gemm(p0.down.n_bands, p0.down.ksteps, nb);
-  const GemmPlan pl_lm = plan_gemm(ctx->lm_head.n_bands, ctx->lm_head.ksteps, nb);
+  const GemmPlan pl_qkv = plan_gemm(p0.qkv.n_bands, p0.qkv.ksteps, nb, ctx->n_cu);
+  const GemmPlan pl_o = plan_gemm(p0.o.n_bands, p0.o.ksteps, nb, ctx->n_cu);
+  const GemmPlan pl_gu = plan_gemm(p0.gu.n_bands, p0.gu.ksteps, nb, ctx->n_cu);
+  const GemmPlan pl_dn = plan_gemm(p0.down.n_bands, p0.down.ksteps, nb, ctx->n_cu);
+  const GemmPlan pl_lm = plan_gemm(ctx->lm_head.n_bands, ctx->lm_head.ksteps, nb, ctx->n_cu);
 
   if (getenv("SPECASR_DEBUG")) {
     const GemmPlan *pls[5] = {&pl_qkv, &pl_o, &pl_gu, &pl_dn, &pl_lm};
     const char *nm[5] = {"qkv", "o", "gate_up", "down", "lm_head"};
     const PackedMatrix *pm[5] = {&p0.qkv, &p0.o, &p0.gu, &p0.down, &ctx->lm_head};
     for (int i = 0; i < 5; ++i)
-      fprintf(stderr, "[specasr] %-8s bands=%d ksteps=%d rows=%d: splits=%d chunk=%d bands/wave=%d\n", nm[i],
-              pm[i]->n_bands, pm[i]->ksteps, R, pls[i]->n_splits, pls[i]->chunk_steps, pls[i]->bands_per_wave);
+      fprintf(stderr, "[specasr] %-8s bands=%d ksteps=%d rows=%d: splits=%d ring=%d grid=%d\n", nm[i],
+              pm[i]->n_bands, pm[i]->ksteps, R, pls[i]->n_splits, pls[i]->lw, pls[i]->grid);
   }
   launch_rope_table(m, md.head_dim, md.rope_theta, cs, st);
   launch_embed(m, 1, ctx->w.tok_embed, tree->input_embeds, ctx->cfg.max_nodes, d, x, st);
@@ -425,7 +420,7 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
     const specasr_layer_weights &lw = ctx->layers[l];
     const PackedLayer &pk = ctx->packed[l];
     launch_residual_norm(x, part, pending, R, pending_ld, lw.attn_norm, d, md.rms_eps, hb, hb_lo, st);
-    gemm_stage(ctx, SPECASR_STAGE_QKV, pl, pk.qkv, hb, hb_lo, d, R, part, pl_qkv, st);
+    gemm_stage(ctx, SPECASR_STAGE_QKV, pl, pk.qkv, hb, R, part, pl_qkv, st);
     if (mfma_attn) {
       launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, ctx->col_k, ctx->col_v, cs, nullptr, qb, qb_lo, kv->k, kv->v, st);
       launch_tree_attention(m, md, g, l, hs.max_total_keys, hs.max_seq_nodes, qb, qb_lo, kv->k, kv->v,
@@ -433,18 +428,18 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
     } else {
       launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, ctx->col_k, ctx->col_v, cs, q, nullptr, nullptr, kv->k, kv->v, st);
       launch_attention_generic(m, md, g, l, q, kv->k, kv->v, att, st);
-      launch_to_bf16(att, (int64_t)R * dq, attb, attb_lo, st);
+      launch_to_bf16(att, R, dq, attb, attb_lo, st);
     }
-    gemm_stage(ctx, SPECASR_STAGE_O, pl, pk.o, attb, attb_lo, dq, R, part, pl_o, st);
+    gemm_stage(ctx, SPECASR_STAGE_O, pl, pk.o, attb, R, part, pl_o, st);
     launch_residual_norm(x, part, pl_o.n_splits, R, pk.o.ldo, lw.ffn_norm, d, md.rms_eps, hb, hb_lo, st);
-    gemm_stage(ctx, SPECASR_STAGE_GATE_UP, pl, pk.gu, hb, hb_lo, d, R, part, pl_gu, st);
+    gemm_stage(ctx, SPECASR_STAGE_GATE_UP, pl, pk.gu, hb, R, part, pl_gu, st);
     launch_swiglu_finish(part, pl_gu.n_splits, R, pk.gu.ldo, ctx->col_up, F, tb, tb_lo, st);
-    gemm_stage(ctx, SPECASR_STAGE_DOWN, pl, pk.down, tb, tb_lo, F, R, part, pl_dn, st);
+    gemm_stage(ctx, SPECASR_STAGE_DOWN, pl, pk.down, tb, R, part, pl_dn, st);
     pending = pl_dn.n_splits;
     pending_ld = pk.down.ldo;
   }
   launch_residual_norm(x, part, pending, R, pending_ld, ctx->w.final_norm, d, md.rms_eps, hb, hb_lo, st);
-  gemm_stage(ctx, SPECASR_STAGE_LM_HEAD, true, ctx->lm_head, hb, hb_lo, d, R, part, pl_lm, st);
+  gemm_stage(ctx, SPECASR_STAGE_LM_HEAD, true, ctx->lm_head, hb, R, part, pl_lm, st);
   launch_logits_argmax(m, part, pl_lm.n_splits, ctx->lm_head.ldo, V, ctx->cfg.max_nodes, logits_dev,
                        (float *)(ws + L.blk_val), (int *)(ws + L.blk_idx), argmax_dev, st);
 }
@@ -468,12 +463,17 @@ specasr_status build_packed(specasr_ctx *ctx) {
   const specasr_config &c = ctx->cfg;
   const int d = c.d_model, F = c.d_ffn, dq = c.n_heads * c.head_dim, dkv = c.n_kv_heads * c.head_dim;
   HIP_TRY(ctx, gemm_skinny_set_lds_limit());
+  {
+    int dev = 0, cus = 0;
+    HIP_TRY(ctx, hipGetDevice(&dev));
+    HIP_TRY(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    if (cus >= 8) ctx->n_cu = cus;
+  }
   auto alloc = [&](PackedMatrix &pm, int n_out_padded, int K) -> hipError_t {
     pm.n_bands = n_out_padded / 32;
-    pm.ksteps = (K / 16 + kGemmU - 1) / kGemmU * kGemmU;
-    pm.k_real = K;
+    pm.ksteps = K / 16;
     pm.ldo = n_out_padded;
-    hipError_t e = hipMalloc(&pm.data, (size_t)n_out_padded * pm.ksteps * 16 * 2);
+    hipError_t e = hipMalloc(&pm.data, (size_t)n_out_padded * K * 2);
     if (e == hipSuccess) ctx->owned.push_back(pm.data);
     return e;
   };
@@ -486,20 +486,20 @@ specasr_status build_packed(specasr_ctx *ctx) {
     const specasr_layer_weights &lw = ctx->layers[l];
     PackedLayer &pk = ctx->packed[l];
     HIP_TRY(ctx, alloc(pk.qkv, ctx->col_v + pad32(dkv), d));
-    launch_repack(lw.wq, dq, d, pk.qkv.ksteps, pk.qkv.data, 0, st);
-    launch_repack(lw.wk, dkv, d, pk.qkv.ksteps, pk.qkv.data, ctx->col_k / 32, st);
-    launch_repack(lw.wv, dkv, d, pk.qkv.ksteps, pk.qkv.data, ctx->col_v / 32, st);
+    launch_repack(lw.wq, dq, d, pk.qkv.data, 0, st);
+    launch_repack(lw.wk, dkv, d, pk.qkv.data, ctx->col_k / 32, st);
+    launch_repack(lw.wv, dkv, d, pk.qkv.data, ctx->col_v / 32, st);
     HIP_TRY(ctx, alloc(pk.o, pad32(d), dq));
-    launch_repack(lw.wo, d, dq, pk.o.ksteps, pk.o.data, 0, st);
+    launch_repack(lw.wo, d, dq, pk.o.data, 0, st);
     HIP_TRY(ctx, alloc(pk.gu, 2 * pad32(F), d));
-    launch_repack(lw.w_gate, F, d, pk.gu.ksteps, pk.gu.data, 0, st);
-    launch_repack(lw.w_up, F, d, pk.gu.ksteps, pk.gu.data, ctx->col_up / 32, st);
+    launch_repack(lw.w_gate, F, d, pk.gu.data, 0, st);
+    launch_repack(lw.w_up, F, d, pk.gu.data, ctx->col_up / 32, st);
     HIP_TRY(ctx, alloc(pk.down, pad32(d), F));
-    launch_repack(lw.w_down, d, F, pk.down.ksteps, pk.down.data, 0, st);
+    launch_repack(lw.w_down, d, F, pk.down.data, 0, st);
     HIP_TRY(ctx, hipGetLastError());
   }
   HIP_TRY(ctx, alloc(ctx->lm_head, pad32(c.vocab), d));
-  launch_repack(ctx->w.lm_head, c.vocab, d, ctx->lm_head.ksteps, ctx->lm_head.data, 0, st);
+  launch_repack(ctx->w.lm_head, c.vocab, d, ctx->lm_head.data, 0, st);
   HIP_TRY(ctx, hipGetLastError());
   HIP_TRY(ctx, hipStreamSynchronize(st));
   // bound of the partial-sum buffer: floats per activation row, over every GEMM and both widths
@@ -508,7 +508,9 @@ specasr_status build_packed(specasr_ctx *ctx) {
   const PackedMatrix *mats[5] = {&p0.qkv, &p0.o, &p0.gu, &p0.down, &ctx->lm_head};
   for (const PackedMatrix *pm : mats)
     for (int nb = 1; nb <= 2; ++nb) {
-      const GemmPlan pl = plan_gemm(pm->n_bands, pm->ksteps, nb);
+      const GemmPlan pl = plan_gemm(pm->n_bands, pm->ksteps, nb, ctx->n_cu);
+      // the longest wavefront slice must fit the ring; otherwise this shape stays on the generic path
+      if (((pm->ksteps + pl.n_splits - 1) / pl.n_splits + 7) / 8 > pl.lw) return SPECASR_E_UNSUPPORTED;
       const size_t need = (size_t)pl.n_splits * pm->ldo;
       if (need > bound) bound = need;
     }
@@ -620,7 +622,12 @@ specasr_status specasr_create(const specasr_config *cfg, const specasr_weights *
                          c.d_ffn % 16 == 0 && (c.n_heads * c.head_dim) % 16 == 0;
   if (want_fast) {
     specasr_status rs = build_packed(ctx);
-    if (rs != SPECASR_OK) {
+    if (rs == SPECASR_E_UNSUPPORTED) {
+      for (void *p : ctx->owned) (void)hipFree(p);
+      ctx->owned.clear();
+      ctx->packed.clear();
+      ctx->fast = false;
+    } else if (rs != SPECASR_OK) {
       const int32_t he = ctx->last_hip;
       specasr_destroy(ctx);
       (void)he;

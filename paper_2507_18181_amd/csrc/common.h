@@ -38,6 +38,12 @@ template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float f) {
   return r;
 }
 
+// Element offset of activation (row, col) inside one plane of a B-operand-packed buffer:
+// [kstep = col/16][node group = row/32][lane = row%32 + 32*((col%16)/8)][col%8]
+__host__ __device__ __forceinline__ int64_t packed_act_offset(int row, int col, int nb) {
+  return ((((int64_t)(col >> 4) * nb + (row >> 5)) * 64 + (row & 31) + 32 * ((col >> 3) & 1)) << 3) + (col & 7);
+}
+
 // ---- per-call tree metadata as the kernels see it ------------------------
 // Rows are the tree nodes of all sequences of the call, flattened without
 // padding: row = row_start[seq] + node.

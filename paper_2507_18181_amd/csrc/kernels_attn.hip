@@ -41,7 +41,7 @@ __global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g
                                                             float *__restrict__ ml_part) {
   constexpr int KK = HD / 16;  // MFMA k-steps across the head dimension
   constexpr int CB = HD / 32;  // 32-wide output column blocks
-  __shared__ uint32_t vp[16 * HD];  // V tile: [key pair][column], low half = even key
+  __shared__ uint32_t vp[2 * 16 * HD];  // two V tiles: [key pair][column], low half = even key
   const int lane = threadIdx.x, h = lane >> 5, ql = lane & 31;
   const int chunk = blockIdx.x, kvh = blockIdx.y / n_rgb, rgb = blockIdx.y % n_rgb, seq = blockIdx.z;
   const int G = H / Hkv;
@@ -85,21 +85,29 @@ __global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g
   const uint16_t *kbase = kc + g.row(seq, layer, kvh, 0);
   const uint16_t *vbase = vc + g.row(seq, layer, kvh, 0);
 
-  for (int t0 = t_begin; t0 < t_end; t0 += 32) {
-    // K tile straight into A-operand registers (keys past the end re-read the last key; masked below)
-    u32x4 kreg[KK];
-    {
-      const uint16_t *kp = kbase + (int64_t)min(t0 + ql, T - 1) * HD + 8 * h;
+  // One 32-key tile in flight while the previous one is computed (register double buffer):
+  // K as A-operand registers, V as raw row pairs that are interleaved into LDS when consumed.
+  constexpr int VI = HD / 32;  // (key pair, 8-column group) items per lane
+  auto issue = [&](int t0, u32x4 (&kreg)[KK], u32x4 (&va)[VI], u32x4 (&vb)[VI]) {
+    const uint16_t *kp = kbase + (int64_t)min(t0 + ql, T - 1) * HD + 8 * h;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) kreg[kk] = *reinterpret_cast<const u32x4 *>(kp + 16 * kk);
-    }
-    // V tile into LDS, two keys interleaved per 32-bit word
-    __syncthreads();
-    for (int it = lane; it < 16 * (HD / 8); it += 64) {
+    for (int kk = 0; kk < KK; ++kk) kreg[kk] = *reinterpret_cast<const u32x4 *>(kp + 16 * kk);
+#pragma unroll
+    for (int x = 0; x < VI; ++x) {
+      const int it = lane + 64 * x;
       const int pair = it / (HD / 8), cg = it - pair * (HD / 8);
       const int k0 = min(t0 + 2 * pair, T - 1), k1 = min(t0 + 2 * pair + 1, T - 1);
-      const u32x4 a = *reinterpret_cast<const u32x4 *>(vbase + (int64_t)k0 * HD + 8 * cg);
-      const u32x4 b = *reinterpret_cast<const u32x4 *>(vbase + (int64_t)k1 * HD + 8 * cg);
+      va[x] = *reinterpret_cast<const u32x4 *>(vbase + (int64_t)k0 * HD + 8 * cg);
+      vb[x] = *reinterpret_cast<const u32x4 *>(vbase + (int64_t)k1 * HD + 8 * cg);
+    }
+  };
+  auto compute = [&](int t0, uint32_t *vpb, const u32x4 (&kreg)[KK], const u32x4 (&va)[VI], const u32x4 (&vb)[VI]) {
+    // V tile into LDS, two keys interleaved per 32-bit word (low half = even key)
+#pragma unroll
+    for (int x = 0; x < VI; ++x) {
+      const int it = lane + 64 * x;
+      const int pair = it / (HD / 8), cg = it - pair * (HD / 8);
+      const u32x4 a = va[x], b = vb[x];
       u32x4 lo, hi;  // columns 8cg..8cg+3 and 8cg+4..8cg+7
       lo[0] = (a[0] & 0xffffu) | (b[0] << 16);
       lo[1] = (a[0] >> 16) | (b[0] & 0xffff0000u);
@@ -109,12 +117,11 @@ __global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g
       hi[1] = (a[2] >> 16) | (b[2] & 0xffff0000u);
       hi[2] = (a[3] & 0xffffu) | (b[3] << 16);
       hi[3] = (a[3] >> 16) | (b[3] & 0xffff0000u);
-      u32x4 *dst = reinterpret_cast<u32x4 *>(vp + pair * HD + 8 * cg);
+      u32x4 *dst = reinterpret_cast<u32x4 *>(vpb + pair * HD + 8 * cg);
       dst[0] = lo;
       dst[1] = hi;
     }
     __syncthreads();
-
 #pragma unroll
     for (int w = 0; w < RGW; ++w) {
       f32x16 sT;
@@ -167,21 +174,31 @@ __global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g
           pl[i2] = (uint32_t)l0 | ((uint32_t)l1 << 16);
         }
         // matching V^T k-slots: key pairs 8*mm + 2*h, +1, 8*mm + 4 + 2*h, +1
-        const uint32_t *vrow = vp + (8 * mm + 2 * h) * HD + ql;
+        const uint32_t *vrow = vpb + (8 * mm + 2 * h) * HD + ql;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
-          u32x4 va;
-          va[0] = vrow[32 * cb];
-          va[1] = vrow[32 * cb + HD];
-          va[2] = vrow[32 * cb + 4 * HD];
-          va[3] = vrow[32 * cb + 5 * HD];
-          o[w][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va),
+          u32x4 vreg;
+          vreg[0] = vrow[32 * cb];
+          vreg[1] = vrow[32 * cb + HD];
+          vreg[2] = vrow[32 * cb + 4 * HD];
+          vreg[3] = vrow[32 * cb + 5 * HD];
+          o[w][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vreg),
                                                              __builtin_bit_cast(bf16x8, pb), o[w][cb], 0, 0, 0);
-          o[w][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va),
+          o[w][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vreg),
                                                              __builtin_bit_cast(bf16x8, pl), o[w][cb], 0, 0, 0);
         }
       }
     }
+  };
+
+  u32x4 kA[KK], vaA[VI], vbA[VI], kB[KK], vaB[VI], vbB[VI];
+  issue(t_begin, kA, vaA, vbA);
+  for (int t0 = t_begin; t0 < t_end; t0 += 64) {
+    const bool hasB = t0 + 32 < t_end;
+    if (hasB) issue(t0 + 32, kB, vaB, vbB);
+    compute(t0, vp, kA, vaA, vbA);
+    if (t0 + 64 < t_end) issue(t0 + 64, kA, vaA, vbA);
+    if (hasB) compute(t0 + 32, vp + 16 * HD, kB, vaB, vbB);
   }
 
   // partial results: O^T lane layout = query column ql, output columns 32*cb + 8*(j/4) + 4*h + j%4
@@ -208,22 +225,42 @@ __global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g
 __global__ void tree_attention_merge_kernel(StepMeta m, int H, int HD, int chunk_keys,
                                             const float *__restrict__ o_part,
                                             const float *__restrict__ ml_part,
-                                            uint16_t *__restrict__ out, uint16_t *__restrict__ out_lo) {
+                                            uint16_t *__restrict__ out, uint16_t *__restrict__ out_lo,
+                                            int nb) {
   const int a = blockIdx.x, r = blockIdx.y, c = threadIdx.x, rows = m.rows;
   const int seq = m.seq[r];
   const int T = m.kv_len[seq] + m.n_nodes[seq];
   const int n_chunks = (T + chunk_keys - 1) / chunk_keys;
-  float M = -INFINITY;
-  for (int ch = 0; ch < n_chunks; ++ch) M = fmaxf(M, ml_part[(((int64_t)ch * rows + r) * H + a) * 2]);
-  float num = 0.f, den = 0.f;
-  for (int ch = 0; ch < n_chunks; ++ch) {
-    const int64_t base = ((int64_t)ch * rows + r) * H + a;
-    const float mc = ml_part[base * 2];
-    const float wgt = (mc == -INFINITY) ? 0.f : __expf(mc - M);
-    num += wgt * o_part[base * HD + c];
-    den += wgt * ml_part[base * 2 + 1];
+  // batches of 8 chunks with all loads issued together; running (max, numerator, denominator)
+  float M = -INFINITY, num = 0.f, den = 0.f;
+  const int64_t cstride = (int64_t)rows * H;
+  const int64_t base0 = (int64_t)r * H + a;
+  for (int c0 = 0; c0 < n_chunks; c0 += 8) {
+    float mc[8], lc[8], oc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int ch = min(c0 + i, n_chunks - 1);
+      const int64_t base = base0 + ch * cstride;
+      mc[i] = (c0 + i < n_chunks) ? ml_part[base * 2] : -INFINITY;
+      lc[i] = ml_part[base * 2 + 1];
+      oc[i] = o_part[base * HD + c];
+    }
+    float Mb = M;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) Mb = fmaxf(Mb, mc[i]);
+    if (Mb == -INFINITY) continue;
+    const float scale = (M == -INFINITY) ? 0.f : __expf(M - Mb);
+    num *= scale;
+    den *= scale;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float wgt = (mc[i] == -INFINITY) ? 0.f : __expf(mc[i] - Mb);
+      num += wgt * oc[i];
+      den += wgt * lc[i];
+    }
+    M = Mb;
   }
-  const int64_t oi = ((int64_t)r * H + a) * HD + c;
+  const int64_t oi = packed_act_offset(r, a * HD + c, nb);  // B-operand order of the output projection
   split_bf16(num / den, out[oi], out_lo[oi]);
 }
 
@@ -243,7 +280,7 @@ static void launch_attn_hd(const StepMeta &m, const ModelDims &md, const KvGeom 
     tree_attention_kernel<HD, 2><<<grid, 64, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, n_rgb, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, o_part, ml_part);
   }
   dim3 mgrid(md.n_heads, m.rows);
-  tree_attention_merge_kernel<<<mgrid, HD, 0, st>>>(m, md.n_heads, HD, chunk_keys, o_part, ml_part, out, out_lo);
+  tree_attention_merge_kernel<<<mgrid, HD, 0, st>>>(m, md.n_heads, HD, chunk_keys, o_part, ml_part, out, out_lo, m.rows <= 32 ? 1 : 2);
 }
 
 bool tree_attention_supported(int head_dim) { return head_dim == 64 || head_dim == 128; }

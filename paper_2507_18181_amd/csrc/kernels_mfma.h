@@ -4,29 +4,25 @@
 
 namespace specasr {
 
-constexpr int kGemmMaxLds = 96 * 1024;  // LDS bytes one skinny-GEMM workgroup may use for activations
-constexpr int kGemmU = 8;                // weight tiles each lane keeps in flight; k-chunks are multiples of it
 
 // A weight matrix repacked into MFMA A-operand tiles: [n_bands][ksteps][64 lanes][8 bf16].
 struct PackedMatrix {
   void *data = nullptr;
   int n_bands = 0;  // bands of 32 output features (last one zero padded)
-  int ksteps = 0;   // k-steps of 16 input features, padded with zero tiles to a multiple of kGemmU
-  int k_real = 0;   // in_features
+  int ksteps = 0;   // in_features / 16
   int ldo = 0;      // n_bands * 32: row stride of the partial-sum output
 };
 
 struct GemmPlan {
-  int n_splits = 1;        // k-chunks (partial sums per output)
-  int chunk_steps = 0;     // k-steps per chunk (the last chunk may be shorter)
-  int bands_per_wave = 1;  // bands each wavefront streams
+  int n_splits = 1;  // k-chunks across workgroups (partial sums per output)
+  int lw = 16;       // ring slots per wavefront: >= its k-slice, one of the instantiated sizes
+  int grid = 256;    // workgroups, a multiple of n_splits (one per compute unit)
 };
 
-void launch_repack(const void *src, int n_out, int K, int ksteps_pad, void *dst, int band0,
-                   hipStream_t st);
+void launch_repack(const void *src, int n_out, int K, void *dst, int band0, hipStream_t st);
 hipError_t gemm_skinny_set_lds_limit();
-void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *X, const uint16_t *Xlo, int ldx,
-                        int rows, float *part, const GemmPlan &plan, hipStream_t st);
+void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *Xp, int rows, float *part,
+                        const GemmPlan &plan, hipStream_t st);
 void launch_residual_norm(float *x, const float *part, int n_splits, int rows, int ldp,
                           const void *gain, int d, float eps, uint16_t *hb, uint16_t *hb_lo,
                           hipStream_t st);
@@ -36,7 +32,7 @@ void launch_qkv_finish(const StepMeta &m, const ModelDims &md, const KvGeom &g, 
                        hipStream_t st);
 void launch_swiglu_finish(const float *part, int n_splits, int rows, int ldp, int col_up, int F,
                           uint16_t *t, uint16_t *t_lo, hipStream_t st);
-void launch_to_bf16(const float *src, int64_t n, uint16_t *dst, uint16_t *dst_lo, hipStream_t st);
+void launch_to_bf16(const float *src, int rows, int K, uint16_t *dst, uint16_t *dst_lo, hipStream_t st);
 int logits_argmax_blocks(int V);
 void launch_logits_argmax(const StepMeta &m, const float *part, int n_splits, int ldp, int V,
                           int max_nodes, float *logits_out, float *blk_val, int *blk_idx,

@@ -6,18 +6,21 @@
 //   * Weights are repacked once (specasr_create) into MFMA-operand order: the matrix is cut into
 //     tiles of 32 output features x 16 input features; one tile is 1 KB laid out exactly as the A
 //     operand of v_mfma_f32_32x32x16_bf16 (lane l holds row l%32, k = 8*(l/32)..+7), and the tiles
-//     of one 32-row band are contiguous along k.  A wavefront therefore streams its band with
-//     one fully coalesced 16-byte load per lane per tile and feeds it to the matrix core with no
-//     shuffle and no LDS round trip.
-//   * The activations (the B operand, <= 64 rows) are tiny: the workgroup stages its k-chunk of
-//     them into LDS once, already in B-operand order, and every wavefront re-reads them from there.
-//     They are carried as TWO bf16 planes, hi = bf16(v) and lo = bf16(v - hi), and every weight
-//     tile is multiplied with both: the products are exact in fp32, so the projections see the
-//     activations to 16 mantissa bits.  The matrix cores have >10x headroom on this stage; the
-//     extra MFMA is what keeps 22-32 layers inside the 2e-2 logit tolerance.
-//   * Work is split over (k-chunk, band group) so that a few thousand wavefronts each stream a
-//     contiguous span with a ring of loads in flight; partial sums over the k-chunks are written
-//     to a small fp32 buffer and reduced, in a fixed order, by the consumer stage.
+//     of one 32-row band are contiguous along k.  A wavefront streams its tiles with one fully
+//     coalesced 16-byte non-temporal load per lane per tile, straight into the matrix core.
+//   * The activations (the B operand, <= 64 rows) are kept by their producers in the matching
+//     B-operand order, as TWO bf16 planes hi = bf16(v) and lo = bf16(v - hi).  Every weight tile is
+//     multiplied with both (products exact in fp32), so the projections see the activations to
+//     16 mantissa bits; the matrix cores have >10x headroom on this stage, and the extra MFMA is
+//     what keeps 22-32 layers inside the 2e-2 logit tolerance.
+//   * One workgroup of 8 wavefronts per compute unit.  The k range is cut into S chunks across
+//     workgroups and each chunk into 8 slices across the wavefronts of a workgroup; a wavefront
+//     keeps the activations of ITS slice in registers for the whole kernel (no LDS traffic in the
+//     inner loop) and walks over the bands of its workgroup.  Slot k of its weight ring always
+//     holds tile k of the slice and is refilled, right after use, with the same tile of the next
+//     band: a whole band-slice of loads stays in flight, across band boundaries, branch-free.
+//   * The 8 slice results of a band are summed through LDS and written as one partial sum per
+//     k-chunk; the consumer stage adds the S partials in fixed order (deterministic, no atomics).
 #include "kernels.h"
 #include "kernels_mfma.h"
 
@@ -31,72 +34,74 @@ __device__ __forceinline__ u32x4 load_stream(const u32x4 *p) { return __builtin_
 
 // --------------------------------------------------------------------------- weight repack
 // dst tile (band, kt), lane l, element i  <-  src[band*32 + l%32][kt*16 + 8*(l/32) + i]
-// Rows >= n_out (padding of the last band) and columns >= K (padding of k to a whole number of
-// kGemmU-tile batches) are zero.  `band0` is the first packed band written, so several source
-// matrices can be concatenated band-aligned into one packed matrix.
-__global__ void repack_kernel(const uint16_t *src, int n_out, int K, int ksteps_pad, uint16_t *dst,
-                              int band0) {
-  const int64_t tile = blockIdx.x;  // over bands * ksteps_pad
-  const int band = (int)(tile / ksteps_pad), kt = (int)(tile - (int64_t)band * ksteps_pad);
+// Rows >= n_out (padding of the last band) are zero.  `band0` is the first packed band written,
+// so several source matrices can be concatenated band-aligned into one packed matrix.
+__global__ void repack_kernel(const uint16_t *src, int n_out, int K, uint16_t *dst, int band0) {
+  const int ksteps = K / 16;
+  const int64_t tile = blockIdx.x;  // over bands * ksteps
+  const int band = (int)(tile / ksteps), kt = (int)(tile - (int64_t)band * ksteps);
   const int l = threadIdx.x;  // 64 lanes
   const int row = band * 32 + (l & 31);
-  const int col = kt * 16 + 8 * (l >> 5);
   u32x4 v = (u32x4){0u, 0u, 0u, 0u};
-  if (row < n_out && col < K) v = *reinterpret_cast<const u32x4 *>(src + (int64_t)row * K + col);
-  reinterpret_cast<u32x4 *>(dst)[((int64_t)(band0 + band) * ksteps_pad + kt) * 64 + l] = v;
+  if (row < n_out) v = *reinterpret_cast<const u32x4 *>(src + (int64_t)row * K + kt * 16 + 8 * (l >> 5));
+  reinterpret_cast<u32x4 *>(dst)[((int64_t)(band0 + band) * ksteps + kt) * 64 + l] = v;
 }
 
-void launch_repack(const void *src, int n_out, int K, int ksteps_pad, void *dst, int band0,
-                   hipStream_t st) {
+void launch_repack(const void *src, int n_out, int K, void *dst, int band0, hipStream_t st) {
   const int bands = (n_out + 31) / 32;
-  const int64_t tiles = (int64_t)bands * ksteps_pad;
-  repack_kernel<<<(unsigned)tiles, 64, 0, st>>>((const uint16_t *)src, n_out, K, ksteps_pad, (uint16_t *)dst, band0);
+  const int64_t tiles = (int64_t)bands * (K / 16);
+  repack_kernel<<<(unsigned)tiles, 64, 0, st>>>((const uint16_t *)src, n_out, K, (uint16_t *)dst, band0);
 }
 
 // --------------------------------------------------------------------------- skinny GEMM
 // part[s][row][o] = sum over k in chunk s of X[row][k] * W[o][k]
-// grid.x = n_splits * n_groups; block = 256 (4 wavefronts); wavefront w of group g owns bands
-// [(g*4+w)*bpw, +bpw).  LDS: X chunk in B-operand order, [kstep][NB][hi|lo][64 lanes] x 16 bytes.
-// Every chunk holds a whole number of U-tile batches (the packed k extent is padded to that), so
-// the steady-state loop is branch-free: U unconditional loads stay in flight per lane, the ring
-// runs on across band boundaries, and at the very end it re-reads the last batch (unused).
-template <int NB, int U>
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4 *__restrict__ Wp,
-                                                          const uint16_t *__restrict__ X,
-                                                          const uint16_t *__restrict__ Xlo, int ldx,
-                                                          int K, float *__restrict__ part, int ldo,
-                                                          int rows, int n_bands, int ksteps_all,
-                                                          int n_splits, int chunk_steps, int bpw) {
-  extern __shared__ u32x4 lds[];
+// grid.x = P (a multiple of S), block = 512.  Workgroup g: chunk s = g % S, bands g/S + j*(P/S).
+// Xp: packed activations [plane hi|lo][kstep][NB][64 lanes] x 16 bytes.  LDS: 2 x 8 x NB x 4 KB.
+template <int NB, int LW>
+__global__ __launch_bounds__(512) void gemm_skinny_kernel(const u32x4 *__restrict__ Wp,
+                                                          const u32x4 *__restrict__ Xp,
+                                                          float *__restrict__ part, int ldo,
+                                                          int rows, int n_bands, int ksteps, int S) {
+  extern __shared__ float red[];  // [2][8][NB * 1024]
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int s = blockIdx.x % n_splits, grp = blockIdx.x / n_splits;
-  const int ks0 = s * chunk_steps;
-  const int nks = min(chunk_steps, ksteps_all - ks0);  // k-steps of this chunk, a multiple of U
-  const int b0 = min((grp * 4 + wave) * bpw, n_bands), b1 = min(b0 + bpw, n_bands);
-  const u32x4 *wbase = Wp + (int64_t)ks0 * 64 + lane;
-  const int64_t band_stride = (int64_t)ksteps_all * 64;
-
-  // start the weight stream before anything else
-  u32x4 buf[U];
-  {
-    const u32x4 *p = wbase + (int64_t)min(b0, n_bands - 1) * band_stride;
+  const int P = gridDim.x;
+  const int s = blockIdx.x % S, bg = blockIdx.x / S, bstride = P / S;
+  // k-chunk of the workgroup and slice of the wavefront, balanced to within one k-step
+  const int c0 = (int)((int64_t)ksteps * s / S), c1 = (int)((int64_t)ksteps * (s + 1) / S);
+  const int w0 = c0 + (int)((int64_t)(c1 - c0) * wave / 8), w1 = c0 + (int)((int64_t)(c1 - c0) * (wave + 1) / 8);
+  const int len = w1 - w0;  // 0 <= len <= LW
+  const int n_units = bg < n_bands ? (n_bands - bg + bstride - 1) / bstride : 0;
+  if (n_units == 0) return;
+  const int64_t band_stride = (int64_t)ksteps * 64;
+  const u32x4 *wbase = Wp + (int64_t)min(w0, ksteps - 1) * 64 + lane;
+  // slot k reads tile min(k, len-1) of the slice (a duplicate beyond the slice: multiplied by zero)
+  int toff[LW];
 #pragma unroll
-    for (int u = 0; u < U; ++u) buf[u] = load_stream(p + 64 * u);
-  }
-  // stage the activation chunk: slot (kstep, nb, l) <- X[nb*32 + l%32][16*(ks0+kstep) + 8*(l/32) ..+7]
-  for (int idx = threadIdx.x; idx < nks * NB * 128; idx += 256) {
-    const int l = idx & 63, blk = idx >> 6;
-    const int part_lo = blk & 1, nb = (blk >> 1) % NB, kstep = (blk >> 1) / NB;
-    const int r = nb * 32 + (l & 31);
-    const int col = 16 * (ks0 + kstep) + 8 * (l >> 5);
-    u32x4 v = (u32x4){0u, 0u, 0u, 0u};
-    if (r < rows && col < K) v = *reinterpret_cast<const u32x4 *>((part_lo ? Xlo : X) + (int64_t)r * ldx + col);
-    lds[idx] = v;
-  }
-  __syncthreads();
+  for (int k = 0; k < LW; ++k) toff[k] = max(min(k, len - 1), 0) * 64;
 
-  for (int band = b0; band < b1; ++band) {
-    // two accumulator sets per node group (hi and lo plane): independent MFMA chains
+  u32x4 buf[LW];
+  {
+    const u32x4 *p = wbase + (int64_t)bg * band_stride;
+#pragma unroll
+    for (int k = 0; k < LW; ++k) buf[k] = load_stream(p + toff[k]);
+  }
+  // activations of the slice, both planes, into registers
+  u32x4 xh[LW][NB], xl[LW][NB];
+  const int64_t plane = (int64_t)ksteps * NB * 64;
+#pragma unroll
+  for (int k = 0; k < LW; ++k)
+#pragma unroll
+    for (int n = 0; n < NB; ++n) {
+      const bool ok = k < len;
+      const int64_t off = ((int64_t)(w0 + k) * NB + n) * 64 + lane;
+      xh[k][n] = ok ? Xp[off] : (u32x4){0u, 0u, 0u, 0u};
+      xl[k][n] = ok ? Xp[plane + off] : (u32x4){0u, 0u, 0u, 0u};
+    }
+
+  for (int unit = 0; unit < n_units; ++unit) {
+    const int band = bg + unit * bstride;
+    const int nband = unit + 1 < n_units ? band + bstride : band;  // the last band is re-read, unused
+    const u32x4 *pn = wbase + (int64_t)nband * band_stride;
     f32x16 acc[NB][2];
 #pragma unroll
     for (int n = 0; n < NB; ++n)
@@ -104,57 +109,65 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const u32x4 *__restric
       for (int h = 0; h < 2; ++h)
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[n][h][j] = 0.f;
-    for (int kb = 0; kb < nks; kb += U) {
-      // where the next batch of this wavefront's stream lives
-      int nband = band, nk = kb + U;
-      if (nk >= nks) { nk = 0; ++nband; }
-      if (nband >= b1) { nband = band; nk = kb; }
-      const u32x4 *pn = wbase + (int64_t)nband * band_stride + (int64_t)nk * 64;
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const bf16x8 a = __builtin_bit_cast(bf16x8, buf[u]);
+    for (int k = 0; k < LW; ++k) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, buf[k]);
 #pragma unroll
-        for (int n = 0; n < NB; ++n) {
-          const bf16x8 bh = __builtin_bit_cast(bf16x8, lds[(((kb + u) * NB + n) * 2) * 64 + lane]);
-          const bf16x8 bl = __builtin_bit_cast(bf16x8, lds[(((kb + u) * NB + n) * 2 + 1) * 64 + lane]);
-          acc[n][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bh, acc[n][0], 0, 0, 0);
-          acc[n][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bl, acc[n][1], 0, 0, 0);
-        }
-        buf[u] = load_stream(pn + 64 * u);  // refill the slot just consumed
+      for (int n = 0; n < NB; ++n) {
+        acc[n][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, xh[k][n]), acc[n][0], 0, 0, 0);
+        acc[n][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, xl[k][n]), acc[n][1], 0, 0, 0);
       }
+      buf[k] = load_stream(pn + toff[k]);  // same tile of the next band
     }
-    // C layout: lane l holds node column l%32 and output rows 8*(j/4) + 4*(l/32) + j%4
+    // sum the 8 slices: C layout = node column l%32, output rows 8*(j/4) + 4*(l/32) + j%4
+    float *mine = red + ((unit & 1) * 8 + wave) * (NB * 1024);
 #pragma unroll
-    for (int n = 0; n < NB; ++n) {
-      const int r = n * 32 + (lane & 31);
-      if (r < rows) {
-        float *dst = part + ((int64_t)s * rows + r) * ldo + band * 32 + 4 * (lane >> 5);
+    for (int n = 0; n < NB; ++n)
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-          *reinterpret_cast<float4 *>(dst + 8 * q) =
-              make_float4(acc[n][0][4 * q] + acc[n][1][4 * q], acc[n][0][4 * q + 1] + acc[n][1][4 * q + 1],
-                          acc[n][0][4 * q + 2] + acc[n][1][4 * q + 2], acc[n][0][4 * q + 3] + acc[n][1][4 * q + 3]);
-      }
+      for (int j = 0; j < 16; ++j) mine[n * 1024 + j * 64 + lane] = acc[n][0][j] + acc[n][1][j];
+    __syncthreads();
+    const float *all = red + (unit & 1) * 8 * (NB * 1024);
+#pragma unroll
+    for (int e2 = 0; e2 < 2 * NB; ++e2) {
+      const int e = threadIdx.x + 512 * e2;
+      float v = 0.f;
+#pragma unroll
+      for (int w = 0; w < 8; ++w) v += all[w * (NB * 1024) + e];
+      const int n = e >> 10, j = (e >> 6) & 15, l = e & 63;
+      const int node = n * 32 + (l & 31), orow = 8 * (j >> 2) + 4 * (l >> 5) + (j & 3);
+      if (node < rows) part[((int64_t)s * rows + node) * ldo + band * 32 + orow] = v;
     }
   }
 }
 
-void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *X, const uint16_t *Xlo, int ldx,
-                        int rows, float *part, const GemmPlan &plan, hipStream_t st) {
-  const int groups = (W.n_bands + 4 * plan.bands_per_wave - 1) / (4 * plan.bands_per_wave);
-  const dim3 grid(groups * plan.n_splits);
+template <int NB, int LW>
+static void launch_gemm_t(const PackedMatrix &W, const uint16_t *Xp, int rows, float *part,
+                          const GemmPlan &plan, hipStream_t st) {
+  const size_t lds = (size_t)2 * 8 * NB * 4096;
+  gemm_skinny_kernel<NB, LW><<<plan.grid, 512, lds, st>>>((const u32x4 *)W.data, (const u32x4 *)Xp, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits);
+}
+
+void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *Xp, int rows, float *part,
+                        const GemmPlan &plan, hipStream_t st) {
   const int nb = rows <= 32 ? 1 : 2;
-  const size_t lds = (size_t)plan.chunk_steps * nb * 2 * 64 * 16;
-  if (nb == 1)
-    gemm_skinny_kernel<1, kGemmU><<<grid, 256, lds, st>>>((const u32x4 *)W.data, X, Xlo, ldx, W.k_real, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits, plan.chunk_steps, plan.bands_per_wave);
-  else
-    gemm_skinny_kernel<2, kGemmU><<<grid, 256, lds, st>>>((const u32x4 *)W.data, X, Xlo, ldx, W.k_real, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits, plan.chunk_steps, plan.bands_per_wave);
+  if (nb == 1) {
+    switch (plan.lw) {
+      case 4: launch_gemm_t<1, 4>(W, Xp, rows, part, plan, st); break;
+      case 8: launch_gemm_t<1, 8>(W, Xp, rows, part, plan, st); break;
+      case 12: launch_gemm_t<1, 12>(W, Xp, rows, part, plan, st); break;
+      default: launch_gemm_t<1, 16>(W, Xp, rows, part, plan, st); break;
+    }
+  } else {
+    if (plan.lw <= 4) launch_gemm_t<2, 4>(W, Xp, rows, part, plan, st);
+    else launch_gemm_t<2, 8>(W, Xp, rows, part, plan, st);
+  }
 }
 
 hipError_t gemm_skinny_set_lds_limit() {
-  hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<1, kGemmU>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmMaxLds);
+  const int big = 2 * 8 * 2 * 4096;
+  hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<2, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute((const void *)gemm_skinny_kernel<2, kGemmU>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmMaxLds);
+  return hipFuncSetAttribute((const void *)gemm_skinny_kernel<2, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
 }
 
 // --------------------------------------------------------------------------- consumers of partial sums
@@ -163,7 +176,7 @@ hipError_t gemm_skinny_set_lds_limit() {
 __global__ __launch_bounds__(1024) void residual_norm_kernel(float *x, const float *part, int n_splits,
                                                              int rows, int ldp, const uint16_t *gain,
                                                              int d, float eps, uint16_t *hb,
-                                                             uint16_t *hb_lo) {
+                                                             uint16_t *hb_lo, int nb) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   float *xr = x + (int64_t)r * d;
@@ -200,9 +213,10 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(float *x, const flo
     uint16_t hi[4], lo[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) split_bf16(y[i], hi[i], lo[i]);
-    *reinterpret_cast<uint2 *>(hb + (int64_t)r * d + c) =
+    const int64_t po = packed_act_offset(r, c, nb);
+    *reinterpret_cast<uint2 *>(hb + po) =
         make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
-    *reinterpret_cast<uint2 *>(hb_lo + (int64_t)r * d + c) =
+    *reinterpret_cast<uint2 *>(hb_lo + po) =
         make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
   }
 }
@@ -210,7 +224,7 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(float *x, const flo
 void launch_residual_norm(float *x, const float *part, int n_splits, int rows, int ldp,
                           const void *gain, int d, float eps, uint16_t *hb, uint16_t *hb_lo,
                           hipStream_t st) {
-  residual_norm_kernel<<<rows, 1024, 0, st>>>(x, part, n_splits, rows, ldp, (const uint16_t *)gain, d, eps, hb, hb_lo);
+  residual_norm_kernel<<<rows, 1024, 0, st>>>(x, part, n_splits, rows, ldp, (const uint16_t *)gain, d, eps, hb, hb_lo, rows <= 32 ? 1 : 2);
 }
 
 // q, k, v = sum of partials; rotary embedding at the node's depth position (Sec. II-B: each
@@ -230,13 +244,20 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(StepMeta m, KvGeom g, i
   const float2 c = cs[(int64_t)r * half + j];
   const float *pr = part + (int64_t)r * ldp;
   const int64_t sstride = (int64_t)rows * ldp;
-  auto val = [&](int col) {
-    float v = 0.f;
-    for (int s = 0; s < n_splits; ++s) v += pr[s * sstride + col];
-    return v;
+  // sums of the split-k partials of up to four columns, loads of one split issued together
+  auto val4 = [&](int c0, int c1, int c2, int c3, float (&out)[4]) {
+    out[0] = out[1] = out[2] = out[3] = 0.f;
+#pragma unroll 4
+    for (int s = 0; s < n_splits; ++s) {
+      const float *q = pr + s * sstride;
+      const float v0 = q[c0], v1 = q[c1], v2 = q[c2], v3 = q[c3];
+      out[0] += v0; out[1] += v1; out[2] += v2; out[3] += v3;
+    }
   };
   if (a < H) {
-    const float x0 = val(a * hd + j), x1 = val(a * hd + j + half);
+    float t[4];
+    val4(a * hd + j, a * hd + j + half, a * hd + j, a * hd + j + half, t);
+    const float x0 = t[0], x1 = t[1];
     const float y0 = x0 * c.x - x1 * c.y, y1 = x1 * c.x + x0 * c.y;
     const int64_t o = ((int64_t)r * H + a) * hd + j;
     if (qb) {
@@ -248,12 +269,14 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(StepMeta m, KvGeom g, i
     }
   } else {
     const int b = a - H;
-    const float x0 = val(col_k + b * hd + j), x1 = val(col_k + b * hd + j + half);
+    float t[4];
+    val4(col_k + b * hd + j, col_k + b * hd + j + half, col_v + b * hd + j, col_v + b * hd + j + half, t);
+    const float x0 = t[0], x1 = t[1];
     const int64_t base = g.row(m.seq[r], layer, b, m.slot[r]);
     kc[base + j] = f32_to_bf16_bits(x0 * c.x - x1 * c.y);
     kc[base + j + half] = f32_to_bf16_bits(x1 * c.x + x0 * c.y);
-    vc[base + j] = f32_to_bf16_bits(val(col_v + b * hd + j));
-    vc[base + j + half] = f32_to_bf16_bits(val(col_v + b * hd + j + half));
+    vc[base + j] = f32_to_bf16_bits(t[2]);
+    vc[base + j + half] = f32_to_bf16_bits(t[3]);
   }
 }
 
@@ -269,11 +292,12 @@ void launch_qkv_finish(const StepMeta &m, const ModelDims &md, const KvGeom &g, 
 // t[r][f] = bf16( silu(sum_s gate) * (sum_s up) ); gate at column f, up at column col_up + f
 __global__ __launch_bounds__(256) void swiglu_finish_kernel(const float *part, int n_splits, int rows,
                                                             int ldp, int col_up, int F, uint16_t *t,
-                                                            uint16_t *t_lo) {
+                                                            uint16_t *t_lo, int nb) {
   const int r = blockIdx.y;
   const int f = (blockIdx.x * 256 + threadIdx.x) * 4;
   if (f >= F) return;
   float4 gt = make_float4(0.f, 0.f, 0.f, 0.f), up = gt;
+#pragma unroll 4
   for (int s = 0; s < n_splits; ++s) {
     const float *p = part + ((int64_t)s * rows + r) * ldp;
     const float4 a = *reinterpret_cast<const float4 *>(p + f);
@@ -286,20 +310,21 @@ __global__ __launch_bounds__(256) void swiglu_finish_kernel(const float *part, i
   uint16_t hi[4], lo[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) split_bf16(y[i], hi[i], lo[i]);
-  *reinterpret_cast<uint2 *>(t + (int64_t)r * F + f) =
+  const int64_t po = packed_act_offset(r, f, nb);
+  *reinterpret_cast<uint2 *>(t + po) =
       make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
-  *reinterpret_cast<uint2 *>(t_lo + (int64_t)r * F + f) =
+  *reinterpret_cast<uint2 *>(t_lo + po) =
       make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
 }
 
 void launch_swiglu_finish(const float *part, int n_splits, int rows, int ldp, int col_up, int F,
                           uint16_t *t, uint16_t *t_lo, hipStream_t st) {
   dim3 grid((F / 4 + 255) / 256, rows);
-  swiglu_finish_kernel<<<grid, 256, 0, st>>>(part, n_splits, rows, ldp, col_up, F, t, t_lo);
+  swiglu_finish_kernel<<<grid, 256, 0, st>>>(part, n_splits, rows, ldp, col_up, F, t, t_lo, rows <= 32 ? 1 : 2);
 }
 
 // fp32 -> bf16 row conversion (attention output feeding the output projection)
-__global__ void to_bf16_kernel(const float *src, int64_t n, uint16_t *dst, uint16_t *dst_lo) {
+__global__ void to_bf16_kernel(const float *src, int64_t n, int K, int nb, uint16_t *dst, uint16_t *dst_lo) {
   int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (i >= n) return;
   const float4 v = *reinterpret_cast<const float4 *>(src + i);
@@ -307,14 +332,17 @@ __global__ void to_bf16_kernel(const float *src, int64_t n, uint16_t *dst, uint1
   uint16_t hi[4], lo[4];
 #pragma unroll
   for (int k = 0; k < 4; ++k) split_bf16(y[k], hi[k], lo[k]);
-  *reinterpret_cast<uint2 *>(dst + i) =
+  const int64_t po = packed_act_offset((int)(i / K), (int)(i % K), nb);
+  *reinterpret_cast<uint2 *>(dst + po) =
       make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
-  *reinterpret_cast<uint2 *>(dst_lo + i) =
+  *reinterpret_cast<uint2 *>(dst_lo + po) =
       make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
 }
 
-void launch_to_bf16(const float *src, int64_t n, uint16_t *dst, uint16_t *dst_lo, hipStream_t st) {
-  to_bf16_kernel<<<(unsigned)((n / 4 + 255) / 256), 256, 0, st>>>(src, n, dst, dst_lo);
+// row-major fp32 [rows][K] -> packed hi/lo planes
+void launch_to_bf16(const float *src, int rows, int K, uint16_t *dst, uint16_t *dst_lo, hipStream_t st) {
+  const int64_t n = (int64_t)rows * K;
+  to_bf16_kernel<<<(unsigned)((n / 4 + 255) / 256), 256, 0, st>>>(src, n, K, rows <= 32 ? 1 : 2, dst, dst_lo);
 }
 
 // logits[r][v] = sum_s part[s][r][v]; per-(row, block) best (value, lowest index); optional
