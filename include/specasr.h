@@ -193,9 +193,9 @@ specasr_status specasr_commit(specasr_ctx *ctx, specasr_kv *kv, const int32_t *n
 int32_t specasr_uses_mfma(const specasr_ctx *ctx, int32_t rows);
 
 /* Measurement aid for benchmarks (no effect on results).  While enabled, every forward
- * brackets ONE launch of the chosen projection GEMM (the layer rotates from call to call) with
- * a pair of HIP events on the caller's stream.  specasr_stage_time waits for the recorded
- * events and returns the accumulated kernel milliseconds and the number of launches measured
+ * launches ONE instance of the chosen projection GEMM (the layer rotates from call to call)
+ * with a pair of HIP events that take the start and stop time of that dispatch on the caller's
+ * stream.  specasr_stage_time waits for the recorded events and returns the accumulated kernel milliseconds and the number of launches measured
  * since profiling was enabled, plus the weight bytes one such launch streams. */
 typedef enum { SPECASR_STAGE_QKV = 0, SPECASR_STAGE_O = 1, SPECASR_STAGE_GATE_UP = 2,
                SPECASR_STAGE_DOWN = 3, SPECASR_STAGE_LM_HEAD = 4 } specasr_stage;

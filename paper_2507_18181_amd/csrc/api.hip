@@ -369,12 +369,10 @@ void gemm_stage(specasr_ctx *ctx, int stage, bool profiled_layer, const PackedMa
   const bool prof = ctx->prof_stage == stage && profiled_layer && !ctx->prof_ev.empty();
   if (prof) {
     if (ctx->prof_used + 2 > ctx->prof_ev.size()) (void)prof_drain(ctx);
-    (void)hipEventRecord(ctx->prof_ev[ctx->prof_used], st);
-  }
-  launch_gemm_skinny(W, Xp, rows, part, plan, st);
-  if (prof) {
-    (void)hipEventRecord(ctx->prof_ev[ctx->prof_used + 1], st);
+    launch_gemm_skinny(W, Xp, rows, part, plan, stage, st, ctx->prof_ev[ctx->prof_used], ctx->prof_ev[ctx->prof_used + 1]);
     ctx->prof_used += 2;
+  } else {
+    launch_gemm_skinny(W, Xp, rows, part, plan, stage, st);
   }
 }
 

@@ -22,7 +22,8 @@ struct GemmPlan {
 void launch_repack(const void *src, int n_out, int K, void *dst, int band0, hipStream_t st);
 hipError_t gemm_skinny_set_lds_limit();
 void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *Xp, int rows, float *part,
-                        const GemmPlan &plan, hipStream_t st);
+                        const GemmPlan &plan, int stage, hipStream_t st,
+                        hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 void launch_residual_norm(float *x, const float *part, int n_splits, int rows, int ldp,
                           const void *gain, int d, float eps, uint16_t *hb, uint16_t *hb_lo,
                           hipStream_t st);

@@ -21,6 +21,8 @@
 //     band: a whole band-slice of loads stays in flight, across band boundaries, branch-free.
 //   * The 8 slice results of a band are summed through LDS and written as one partial sum per
 //     k-chunk; the consumer stage adds the S partials in fixed order (deterministic, no atomics).
+#include <hip/hip_ext.h>
+
 #include "kernels.h"
 #include "kernels_mfma.h"
 
@@ -57,7 +59,9 @@ void launch_repack(const void *src, int n_out, int K, void *dst, int band0, hipS
 // part[s][row][o] = sum over k in chunk s of X[row][k] * W[o][k]
 // grid.x = P (a multiple of S), block = 512.  Workgroup g: chunk s = g % S, bands g/S + j*(P/S).
 // Xp: packed activations [plane hi|lo][kstep][NB][64 lanes] x 16 bytes.  LDS: 2 x 8 x NB x 4 KB.
-template <int NB, int LW>
+// STAGE only names the projection (0 qkv, 1 o, 2 gate|up, 3 down, 4 LM head) so that a profiler
+// lists each of them as its own kernel; the code is identical.
+template <int NB, int LW, int STAGE>
 __global__ __launch_bounds__(512) void gemm_skinny_kernel(const u32x4 *__restrict__ Wp,
                                                           const u32x4 *__restrict__ Xp,
                                                           float *__restrict__ part, int ldo,
@@ -140,34 +144,60 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(const u32x4 *__restric
   }
 }
 
-template <int NB, int LW>
+template <int NB, int LW, int STAGE>
 static void launch_gemm_t(const PackedMatrix &W, const uint16_t *Xp, int rows, float *part,
-                          const GemmPlan &plan, hipStream_t st) {
+                          const GemmPlan &plan, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const size_t lds = (size_t)2 * 8 * NB * 4096;
-  gemm_skinny_kernel<NB, LW><<<plan.grid, 512, lds, st>>>((const u32x4 *)W.data, (const u32x4 *)Xp, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits);
+  if (ev0 != nullptr)  // the events take the start and stop time of this dispatch itself
+    hipExtLaunchKernelGGL((gemm_skinny_kernel<NB, LW, STAGE>), dim3(plan.grid), dim3(512), (uint32_t)lds, st, ev0, ev1, 0u,
+                          (const u32x4 *)W.data, (const u32x4 *)Xp, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits);
+  else
+    gemm_skinny_kernel<NB, LW, STAGE><<<plan.grid, 512, lds, st>>>((const u32x4 *)W.data, (const u32x4 *)Xp, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits);
 }
 
-void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *Xp, int rows, float *part,
-                        const GemmPlan &plan, hipStream_t st) {
-  const int nb = rows <= 32 ? 1 : 2;
-  if (nb == 1) {
+template <int STAGE>
+static void launch_gemm_s(const PackedMatrix &W, const uint16_t *Xp, int rows, float *part,
+                          const GemmPlan &plan, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  if (rows <= 32) {
     switch (plan.lw) {
-      case 4: launch_gemm_t<1, 4>(W, Xp, rows, part, plan, st); break;
-      case 8: launch_gemm_t<1, 8>(W, Xp, rows, part, plan, st); break;
-      case 12: launch_gemm_t<1, 12>(W, Xp, rows, part, plan, st); break;
-      default: launch_gemm_t<1, 16>(W, Xp, rows, part, plan, st); break;
+      case 4: launch_gemm_t<1, 4, STAGE>(W, Xp, rows, part, plan, st, ev0, ev1); break;
+      case 8: launch_gemm_t<1, 8, STAGE>(W, Xp, rows, part, plan, st, ev0, ev1); break;
+      case 12: launch_gemm_t<1, 12, STAGE>(W, Xp, rows, part, plan, st, ev0, ev1); break;
+      default: launch_gemm_t<1, 16, STAGE>(W, Xp, rows, part, plan, st, ev0, ev1); break;
     }
   } else {
-    if (plan.lw <= 4) launch_gemm_t<2, 4>(W, Xp, rows, part, plan, st);
-    else launch_gemm_t<2, 8>(W, Xp, rows, part, plan, st);
+    if (plan.lw <= 4) launch_gemm_t<2, 4, STAGE>(W, Xp, rows, part, plan, st, ev0, ev1);
+    else launch_gemm_t<2, 8, STAGE>(W, Xp, rows, part, plan, st, ev0, ev1);
   }
 }
 
-hipError_t gemm_skinny_set_lds_limit() {
+void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *Xp, int rows, float *part,
+                        const GemmPlan &plan, int stage, hipStream_t st, hipEvent_t ev0,
+                        hipEvent_t ev1) {
+  switch (stage) {
+    case 0: launch_gemm_s<0>(W, Xp, rows, part, plan, st, ev0, ev1); break;
+    case 1: launch_gemm_s<1>(W, Xp, rows, part, plan, st, ev0, ev1); break;
+    case 2: launch_gemm_s<2>(W, Xp, rows, part, plan, st, ev0, ev1); break;
+    case 3: launch_gemm_s<3>(W, Xp, rows, part, plan, st, ev0, ev1); break;
+    default: launch_gemm_s<4>(W, Xp, rows, part, plan, st, ev0, ev1); break;
+  }
+}
+
+template <int STAGE>
+static hipError_t set_lds_s() {
   const int big = 2 * 8 * 2 * 4096;
-  hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<2, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
+  hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<2, 4, STAGE>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute((const void *)gemm_skinny_kernel<2, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
+  return hipFuncSetAttribute((const void *)gemm_skinny_kernel<2, 8, STAGE>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
+}
+
+hipError_t gemm_skinny_set_lds_limit() {
+  hipError_t e = set_lds_s<0>();
+  if (e == hipSuccess) e = set_lds_s<1>();
+  if (e == hipSuccess) e = set_lds_s<2>();
+  if (e == hipSuccess) e = set_lds_s<3>();
+  if (e == hipSuccess) e = set_lds_s<4>();
+  return e;
 }
 
 // --------------------------------------------------------------------------- consumers of partial sums
