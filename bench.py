@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--workload", default="cfg3_7b_n32")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-reps", type=int, default=3)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known traffic, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--stage", default="gate_up", choices=["qkv", "o", "gate_up", "down", "lm_head"])
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -107,6 +110,12 @@ def main():
     def step():
         return step_with(tokens)
 
+    if args.calib_copy:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").fill_(1.0)
+        b = torch.empty_like(a)
+        b.copy_(a)                      # 1 GiB read + 1 GiB written
+        torch.cuda.synchronize()
+        del a, b
     log("warm-up")
     for _ in range(args.warmup):
         out = step()
