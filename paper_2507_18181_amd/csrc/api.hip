@@ -461,6 +461,7 @@ specasr_status build_packed(specasr_ctx *ctx) {
   const specasr_config &c = ctx->cfg;
   const int d = c.d_model, F = c.d_ffn, dq = c.n_heads * c.head_dim, dkv = c.n_kv_heads * c.head_dim;
   HIP_TRY(ctx, gemm_skinny_set_lds_limit());
+  HIP_TRY(ctx, tree_attention_set_lds_limit());
   {
     int dev = 0, cus = 0;
     HIP_TRY(ctx, hipGetDevice(&dev));

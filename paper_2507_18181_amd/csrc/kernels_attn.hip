@@ -16,6 +16,8 @@
 //                                                   which is exactly how the lanes already hold P
 //
 // Partial (unnormalised) outputs per key chunk are merged by a second small kernel.
+#include <cstdlib>
+
 #include "kernels.h"
 #include "kernels_mfma.h"
 
@@ -29,9 +31,12 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
 }
 
-// grid (n_chunks, Hkv * n_rgb, batch), block 64.  RGW = query row groups (of 32) per wavefront.
+// grid (n_chunks, Hkv * n_rgb, batch), block 256: the four wavefronts of a workgroup take the
+// 32-key tiles of the chunk round-robin, each with its own online softmax, and merge their
+// (max, sum, output) through LDS into ONE partial result per chunk.  RGW = query row groups (of
+// 32) per workgroup.
 template <int HD, int RGW>
-__global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g, int layer, int H,
+__global__ __launch_bounds__(256) void tree_attention_kernel(StepMeta m, KvGeom g, int layer, int H,
                                                             int Hkv, int n_rgb,
                                                             const uint16_t *__restrict__ qb,
                                                             const uint16_t *__restrict__ qb_lo,
@@ -41,8 +46,12 @@ __global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g
                                                             float *__restrict__ ml_part) {
   constexpr int KK = HD / 16;  // MFMA k-steps across the head dimension
   constexpr int CB = HD / 32;  // 32-wide output column blocks
-  __shared__ uint32_t vp[2 * 16 * HD];  // two V tiles: [key pair][column], low half = even key
-  const int lane = threadIdx.x, h = lane >> 5, ql = lane & 31;
+  // LDS: per wavefront two V tiles [key pair][column] (low half = even key); reused afterwards
+  // for the cross-wavefront merge: o[wave][rg][cb][j][lane] floats, then (m, l)[wave][rg][32]
+  extern __shared__ uint32_t lds_attn[];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  uint32_t *vp = lds_attn + wave * (2 * 16 * HD);
+  const int lane = threadIdx.x & 63, h = lane >> 5, ql = lane & 31;
   const int chunk = blockIdx.x, kvh = blockIdx.y / n_rgb, rgb = blockIdx.y % n_rgb, seq = blockIdx.z;
   const int G = H / Hkv;
   const int L = m.kv_len[seq], n = m.n_nodes[seq], r0 = m.row_start[seq], rows = m.rows;
@@ -121,27 +130,36 @@ __global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g
       dst[0] = lo;
       dst[1] = hi;
     }
-    __syncthreads();
+    // only this wavefront reads the tile back: its own LDS operations stay in program order
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int w = 0; w < RGW; ++w) {
-      f32x16 sT;
+      f32x16 sT, sT2;  // hi and lo query planes on separate accumulators (independent chains)
 #pragma unroll
-      for (int j = 0; j < 16; ++j) sT[j] = 0.f;
+      for (int j = 0; j < 16; ++j) { sT[j] = 0.f; sT2[j] = 0.f; }
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
         sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[kk]),
                                                      __builtin_bit_cast(bf16x8, qreg[w][kk]), sT, 0, 0, 0);
-        sT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[kk]),
-                                                     __builtin_bit_cast(bf16x8, qlo[w][kk]), sT, 0, 0, 0);
+        sT2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[kk]),
+                                                      __builtin_bit_cast(bf16x8, qlo[w][kk]), sT2, 0, 0, 0);
       }
       // lane holds, for query ql, the keys t0 + 8*(j/4) + 4*h + j%4
       float mx = -INFINITY;
+      if (t0 + 32 <= L) {  // tile inside the prefix: every key visible to every valid query
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int key = t0 + 8 * (j >> 2) + 4 * h + (j & 3);
-        const bool vis = valid[w] && key < T && (key < L || ((anc[w] >> ((key - L) & 63)) & 1ull));
-        sT[j] = vis ? sT[j] : -INFINITY;
-        mx = fmaxf(mx, sT[j]);
+        for (int j = 0; j < 16; ++j) {
+          sT[j] = valid[w] ? sT[j] + sT2[j] : -INFINITY;
+          mx = fmaxf(mx, sT[j]);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const int key = t0 + 8 * (j >> 2) + 4 * h + (j & 3);
+          const bool vis = valid[w] && key < T && (key < L || ((anc[w] >> ((key - L) & 63)) & 1ull));
+          sT[j] = vis ? sT[j] + sT2[j] : -INFINITY;
+          mx = fmaxf(mx, sT[j]);
+        }
       }
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float m_new = fmaxf(m_run[w], mx);
@@ -154,12 +172,15 @@ __global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g
         psum += p[j];
       }
       psum += __shfl_xor(psum, 32, 64);
+      const bool rescale = alpha != 1.0f && l_run[w] != 0.f;  // something accumulated and the max moved
       l_run[w] = l_run[w] * alpha + psum;
       m_run[w] = m_new;
+      if (__ballot(rescale) != 0ull) {
 #pragma unroll
-      for (int cb = 0; cb < CB; ++cb)
+        for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) o[w][cb][j] *= alpha;
+          for (int j = 0; j < 16; ++j) o[w][cb][j] *= alpha;
+      }
       // P^T as B operand: MFMA mm covers keys 16*mm .. 16*mm+15 of the tile; this lane's k-slots
       // i = 0..7 are keys 16*mm + 8*(i/4) + 4*h + i%4, i.e. its own p[8*mm + i]
 #pragma unroll
@@ -192,30 +213,64 @@ __global__ __launch_bounds__(64) void tree_attention_kernel(StepMeta m, KvGeom g
   };
 
   u32x4 kA[KK], vaA[VI], vbA[VI], kB[KK], vaB[VI], vbB[VI];
-  issue(t_begin, kA, vaA, vbA);
-  for (int t0 = t_begin; t0 < t_end; t0 += 64) {
-    const bool hasB = t0 + 32 < t_end;
-    if (hasB) issue(t0 + 32, kB, vaB, vbB);
+  const int t_first = t_begin + 32 * wave;  // this wavefront's tiles: t_first, +128, +256, ...
+  if (t_first < t_end) issue(t_first, kA, vaA, vbA);
+  for (int t0 = t_first; t0 < t_end; t0 += 256) {
+    const bool hasB = t0 + 128 < t_end;
+    if (hasB) issue(t0 + 128, kB, vaB, vbB);
     compute(t0, vp, kA, vaA, vbA);
-    if (t0 + 64 < t_end) issue(t0 + 64, kA, vaA, vbA);
-    if (hasB) compute(t0 + 32, vp + 16 * HD, kB, vaB, vbB);
+    if (t0 + 256 < t_end) issue(t0 + 256, kA, vaA, vbA);
+    if (hasB) compute(t0 + 128, vp + 16 * HD, kB, vaB, vbB);
   }
 
-  // partial results: O^T lane layout = query column ql, output columns 32*cb + 8*(j/4) + 4*h + j%4
+  // merge the four wavefronts: everything to LDS in register layout, then wavefront cb reduces
+  // column block cb and writes the workgroup's partial result
+  __syncthreads();
+  float *lo_ = reinterpret_cast<float *>(lds_attn);
+  float *lml = lo_ + 4 * RGW * CB * 1024;
 #pragma unroll
   for (int w = 0; w < RGW; ++w) {
-    if (!valid[w]) continue;
-    const int64_t base = ((int64_t)chunk * rows + out_row[w]) * H + out_head[w];
-    float *op = o_part + base * HD + 4 * h;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4)
-        *reinterpret_cast<float4 *>(op + 32 * cb + 8 * q4) =
-            make_float4(o[w][cb][4 * q4], o[w][cb][4 * q4 + 1], o[w][cb][4 * q4 + 2], o[w][cb][4 * q4 + 3]);
+      for (int j = 0; j < 16; ++j) lo_[(((wave * RGW + w) * CB + cb) * 16 + j) * 64 + lane] = o[w][cb][j];
     if (h == 0) {
-      ml_part[base * 2] = m_run[w];
-      ml_part[base * 2 + 1] = l_run[w];
+      lml[((wave * RGW + w) * 32 + ql) * 2] = m_run[w];
+      lml[((wave * RGW + w) * 32 + ql) * 2 + 1] = l_run[w];
+    }
+  }
+  __syncthreads();
+  if (wave < CB) {
+    const int cb = wave;
+#pragma unroll
+    for (int w = 0; w < RGW; ++w) {
+      float mw[4], M = -INFINITY;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        mw[v] = lml[((v * RGW + w) * 32 + ql) * 2];
+        M = fmaxf(M, mw[v]);
+      }
+      float Lsum = 0.f, acc[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const float wgt = (mw[v] == -INFINITY) ? 0.f : __expf(mw[v] - M);
+        Lsum += wgt * lml[((v * RGW + w) * 32 + ql) * 2 + 1];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[j] += wgt * lo_[(((v * RGW + w) * CB + cb) * 16 + j) * 64 + lane];
+      }
+      if (!valid[w]) continue;
+      // O^T lane layout = query column ql, output columns 32*cb + 8*(j/4) + 4*h + j%4
+      const int64_t base = ((int64_t)chunk * rows + out_row[w]) * H + out_head[w];
+      float *op = o_part + base * HD + 32 * cb + 4 * h;
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4)
+        *reinterpret_cast<float4 *>(op + 8 * q4) = make_float4(acc[4 * q4], acc[4 * q4 + 1], acc[4 * q4 + 2], acc[4 * q4 + 3]);
+      if (cb == 0 && h == 0) {
+        ml_part[base * 2] = M;
+        ml_part[base * 2 + 1] = Lsum;
+      }
     }
   }
 }
@@ -271,13 +326,19 @@ static void launch_attn_hd(const StepMeta &m, const ModelDims &md, const KvGeom 
                            float *ml_part, uint16_t *out, uint16_t *out_lo, hipStream_t st) {
   const int G = md.n_heads / md.n_kv_heads;
   const int row_groups = (G * max_seq_nodes + 31) / 32;
+  // LDS: 4 wavefronts x 2 V tiles, reused for the merge (4 x RGW x HD/32 x 4 KB + (m, l))
+  auto lds_bytes = [](int rgw) {
+    const size_t vt = (size_t)4 * 2 * 16 * HD * 4;
+    const size_t mg = (size_t)4 * rgw * (HD / 32) * 4096 + (size_t)4 * rgw * 32 * 2 * 4;
+    return vt > mg ? vt : mg;
+  };
   if (row_groups <= 1) {
     dim3 grid(n_chunks, md.n_kv_heads, m.batch);
-    tree_attention_kernel<HD, 1><<<grid, 64, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, 1, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, o_part, ml_part);
+    tree_attention_kernel<HD, 1><<<grid, 256, lds_bytes(1), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, 1, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, o_part, ml_part);
   } else {
     const int n_rgb = (row_groups + 1) / 2;
     dim3 grid(n_chunks, md.n_kv_heads * n_rgb, m.batch);
-    tree_attention_kernel<HD, 2><<<grid, 64, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, n_rgb, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, o_part, ml_part);
+    tree_attention_kernel<HD, 2><<<grid, 256, lds_bytes(2), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, n_rgb, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, o_part, ml_part);
   }
   dim3 mgrid(md.n_heads, m.rows);
   tree_attention_merge_kernel<<<mgrid, HD, 0, st>>>(m, md.n_heads, HD, chunk_keys, o_part, ml_part, out, out_lo, m.rows <= 32 ? 1 : 2);
@@ -285,13 +346,26 @@ static void launch_attn_hd(const StepMeta &m, const ModelDims &md, const KvGeom 
 
 bool tree_attention_supported(int head_dim) { return head_dim == 64 || head_dim == 128; }
 
-int tree_attention_max_chunks(int n_kv_heads) { return 512 / n_kv_heads + 2; }
+int tree_attention_max_chunks(int n_kv_heads) { return 256 / n_kv_heads + 2; }
 
-// Key-chunk size (a multiple of 32) aiming at ~512 wavefronts for the longest sequence.
+hipError_t tree_attention_set_lds_limit() {
+  const int big = 4 * 2 * 4 * 4096 + 4 * 2 * 32 * 2 * 4;  // RGW = 2, head_dim 128
+  hipError_t e = hipFuncSetAttribute((const void *)tree_attention_kernel<128, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void *)tree_attention_kernel<128, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute((const void *)tree_attention_kernel<64, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
+}
+
+// Key-chunk size (a multiple of 32) aiming at ~256 workgroups for the longest sequence.
 int tree_attention_chunk_keys(int max_total_keys, int n_kv_heads, int batch, int row_group_blocks) {
-  long want = ((long)max_total_keys * n_kv_heads * batch * row_group_blocks + 511) / 512;
+  long want = ((long)max_total_keys * n_kv_heads * batch * row_group_blocks + 255) / 256;
   long ck = (want + 31) / 32 * 32;
   if (ck < 32) ck = 32;
+  if (const char *e = getenv("SPECASR_ATTN_CHUNK")) {  // tuning aid: never below the automatic size
+    const long v = atol(e) / 32 * 32;
+    if (v > ck) ck = v;
+  }
   return (int)ck;
 }
 

@@ -357,6 +357,8 @@ void launch_accept(const StepMeta &m, int max_nodes, const int32_t *argmax, int3
 // (sequence, layer, KV head, K|V) per block.  Since path is strictly increasing with
 // path[k] >= k, a destination slot may be another move's source: every source row is read
 // into registers, the block synchronises, and only then is anything written.
+typedef __attribute__((ext_vector_type(4))) uint32_t mv16_t;  // one 16-byte unit of a cache row
+
 template <int UNITS>
 __global__ __launch_bounds__(256) void compact_kernel(KvGeom g, int max_nodes, int row_bytes,
                                                       const int32_t *kv_len, const int32_t *path,
@@ -373,14 +375,15 @@ __global__ __launch_bounds__(256) void compact_kernel(KvGeom g, int max_nodes, i
   const int upr = row_bytes / 16;  // 16-byte units per row
   const int total = len * upr;
   if (total <= 256 * UNITS) {
-    uint4 regs[UNITS];
+    mv16_t regs[UNITS];
 #pragma unroll
     for (int i = 0; i < UNITS; ++i) {
       int u = threadIdx.x + i * 256;
       if (u < total) {
         int k = u / upr, w = u - k * upr;
         int src = p[k];
-        if (src != k) regs[i] = *reinterpret_cast<const uint4 *>(base + (int64_t)src * row_bytes + w * 16);
+        regs[i] = (mv16_t){0u, 0u, 0u, 0u};
+        if (src != k) regs[i] = *reinterpret_cast<const mv16_t *>(base + (int64_t)src * row_bytes + w * 16);
       }
     }
     __syncthreads();
@@ -389,7 +392,7 @@ __global__ __launch_bounds__(256) void compact_kernel(KvGeom g, int max_nodes, i
       int u = threadIdx.x + i * 256;
       if (u < total) {
         int k = u / upr, w = u - k * upr;
-        if (p[k] != k) *reinterpret_cast<uint4 *>(base + (int64_t)k * row_bytes + w * 16) = regs[i];
+        if (p[k] != k) *reinterpret_cast<mv16_t *>(base + (int64_t)k * row_bytes + w * 16) = regs[i];
       }
     }
   } else {
@@ -398,14 +401,13 @@ __global__ __launch_bounds__(256) void compact_kernel(KvGeom g, int max_nodes, i
     for (int k = 0; k < len; ++k) {
       int src = p[k];
       if (src == k) continue;
-      uint4 v[2];
-      int cnt = 0;
-      for (int w = threadIdx.x; w < upr && cnt < 2; w += 256)
-        v[cnt++] = *reinterpret_cast<const uint4 *>(base + (int64_t)src * row_bytes + w * 16);
+      // one row is at most 1 KB = 64 units: every thread moves at most one
+      mv16_t v = (mv16_t){0u, 0u, 0u, 0u};
+      if ((int)threadIdx.x < upr)
+        v = *reinterpret_cast<const mv16_t *>(base + (int64_t)src * row_bytes + threadIdx.x * 16);
       __syncthreads();
-      cnt = 0;
-      for (int w = threadIdx.x; w < upr && cnt < 2; w += 256)
-        *reinterpret_cast<uint4 *>(base + (int64_t)k * row_bytes + w * 16) = v[cnt++];
+      if ((int)threadIdx.x < upr)
+        *reinterpret_cast<mv16_t *>(base + (int64_t)k * row_bytes + threadIdx.x * 16) = v;
       __syncthreads();
     }
   }

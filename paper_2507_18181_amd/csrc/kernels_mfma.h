@@ -42,6 +42,7 @@ void launch_logits_argmax(const StepMeta &m, const float *part, int n_splits, in
 // tree-masked MFMA attention (kernels_attn.hip)
 bool tree_attention_supported(int head_dim);
 int tree_attention_max_chunks(int n_kv_heads);
+hipError_t tree_attention_set_lds_limit();
 void launch_tree_attention(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
                            int max_total_keys, int max_seq_nodes, const uint16_t *qb,
                            const uint16_t *qb_lo, const void *kc, const void *vc, float *o_part,
