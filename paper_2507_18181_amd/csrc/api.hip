@@ -395,12 +395,25 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
   uint16_t *qb = (uint16_t *)(ws + L.qb), *qb_lo = qb + (size_t)R * dq;
   const bool mfma_attn = tree_attention_supported(md.head_dim);
   const PackedLayer &p0 = ctx->packed[0];
-  const GemmPlan pl_qkv = plan_gemm(p0.qkv.n_bands, p0.qkv.ksteps, nb, ctx->n_cu);
-  const GemmPlan pl_o = plan_gemm(p0.o.n_bands, p0.o.ksteps, nb, ctx->n_cu);
-  const GemmPlan pl_gu = plan_gemm(p0.gu.n_bands, p0.gu.ksteps, nb, ctx->n_cu);
-  const GemmPlan pl_dn = plan_gemm(p0.down.n_bands, p0.down.ksteps, nb, ctx->n_cu);
-  const GemmPlan pl_lm = plan_gemm(ctx->lm_head.n_bands, ctx->lm_head.ksteps, nb, ctx->n_cu);
+  GemmPlan pl_qkv = plan_gemm(p0.qkv.n_bands, p0.qkv.ksteps, nb, ctx->n_cu);
+  GemmPlan pl_o = plan_gemm(p0.o.n_bands, p0.o.ksteps, nb, ctx->n_cu);
+  GemmPlan pl_gu = plan_gemm(p0.gu.n_bands, p0.gu.ksteps, nb, ctx->n_cu);
+  GemmPlan pl_dn = plan_gemm(p0.down.n_bands, p0.down.ksteps, nb, ctx->n_cu);
+  GemmPlan pl_lm = plan_gemm(ctx->lm_head.n_bands, ctx->lm_head.ksteps, nb, ctx->n_cu);
 
+  if (const char *e = getenv("SPECASR_GEMM_SPLITS")) {  // tuning aid: "qkv,o,gate_up,down,lm_head" split counts
+    int v[5] = {0, 0, 0, 0, 0};
+    sscanf(e, "%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4]);
+    GemmPlan *pls[5] = {&pl_qkv, &pl_o, &pl_gu, &pl_dn, &pl_lm};
+    const PackedMatrix *pm[5] = {&p0.qkv, &p0.o, &p0.gu, &p0.down, &ctx->lm_head};
+    for (int i = 0; i < 5; ++i) {
+      if (v[i] < 1 || ctx->n_cu % v[i]) continue;
+      const int len = ((pm[i]->ksteps + v[i] - 1) / v[i] + 7) / 8;
+      if (len > (nb == 1 ? 16 : 8) || (size_t)v[i] * pm[i]->ldo > ctx->part_floats) continue;
+      pls[i]->n_splits = v[i];
+      pls[i]->lw = nb == 1 ? (len <= 4 ? 4 : len <= 8 ? 8 : len <= 12 ? 12 : 16) : (len <= 4 ? 4 : 8);
+    }
+  }
   if (getenv("SPECASR_DEBUG")) {
     const GemmPlan *pls[5] = {&pl_qkv, &pl_o, &pl_gu, &pl_dn, &pl_lm};
     const char *nm[5] = {"qkv", "o", "gate_up", "down", "lm_head"};

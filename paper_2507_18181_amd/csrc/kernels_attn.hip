@@ -332,9 +332,10 @@ static void launch_attn_hd(const StepMeta &m, const ModelDims &md, const KvGeom 
     const size_t mg = (size_t)4 * rgw * (HD / 32) * 4096 + (size_t)4 * rgw * 32 * 2 * 4;
     return vt > mg ? vt : mg;
   };
-  if (row_groups <= 1) {
-    dim3 grid(n_chunks, md.n_kv_heads, m.batch);
-    tree_attention_kernel<HD, 1><<<grid, 256, lds_bytes(1), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, 1, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, o_part, ml_part);
+  // two row groups per workgroup only where their accumulators fit the register file (head_dim 64)
+  if (row_groups <= 1 || HD > 64) {
+    dim3 grid(n_chunks, md.n_kv_heads * row_groups, m.batch);
+    tree_attention_kernel<HD, 1><<<grid, 256, lds_bytes(1), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, row_groups, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, o_part, ml_part);
   } else {
     const int n_rgb = (row_groups + 1) / 2;
     dim3 grid(n_chunks, md.n_kv_heads * n_rgb, m.batch);
@@ -353,6 +354,8 @@ hipError_t tree_attention_set_lds_limit() {
   hipError_t e = hipFuncSetAttribute((const void *)tree_attention_kernel<128, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute((const void *)tree_attention_kernel<128, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void *)tree_attention_kernel<64, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
   if (e != hipSuccess) return e;
   return hipFuncSetAttribute((const void *)tree_attention_kernel<64, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
 }
@@ -375,7 +378,7 @@ void launch_tree_attention(const StepMeta &m, const ModelDims &md, const KvGeom 
                            float *ml_part, uint16_t *out, uint16_t *out_lo, hipStream_t st) {
   const int G = md.n_heads / md.n_kv_heads;
   const int row_groups = (G * max_seq_nodes + 31) / 32;
-  const int n_rgb = row_groups <= 1 ? 1 : (row_groups + 1) / 2;
+  const int n_rgb = (row_groups <= 1 || md.head_dim > 64) ? row_groups : (row_groups + 1) / 2;
   const int ck = tree_attention_chunk_keys(max_total_keys, md.n_kv_heads, m.batch, n_rgb);
   const int n_chunks = (max_total_keys + ck - 1) / ck;
   if (md.head_dim == 64)
