@@ -131,15 +131,18 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(const u32x4 *__restric
       for (int j = 0; j < 16; ++j) mine[n * 1024 + j * 64 + lane] = acc[n][0][j] + acc[n][1][j];
     __syncthreads();
     const float *all = red + (unit & 1) * 8 * (NB * 1024);
+    // thread (n, q, l) sums output rows 8q + 4*(l/32) + 0..3 of node n*32 + l%32: one 16-byte store
+    if ((int)threadIdx.x < NB * 256) {
+      const int n = threadIdx.x >> 8, q = (threadIdx.x >> 6) & 3, l = threadIdx.x & 63;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-    for (int e2 = 0; e2 < 2 * NB; ++e2) {
-      const int e = threadIdx.x + 512 * e2;
-      float v = 0.f;
-#pragma unroll
-      for (int w = 0; w < 8; ++w) v += all[w * (NB * 1024) + e];
-      const int n = e >> 10, j = (e >> 6) & 15, l = e & 63;
-      const int node = n * 32 + (l & 31), orow = 8 * (j >> 2) + 4 * (l >> 5) + (j & 3);
-      if (node < rows) part[((int64_t)s * rows + node) * ldo + band * 32 + orow] = v;
+      for (int w = 0; w < 8; ++w) {
+        const float *src = all + w * (NB * 1024) + n * 1024 + (4 * q) * 64 + l;
+        v.x += src[0]; v.y += src[64]; v.z += src[128]; v.w += src[192];
+      }
+      const int node = n * 32 + (l & 31);
+      if (node < rows)
+        *reinterpret_cast<float4 *>(part + ((int64_t)s * rows + node) * ldo + band * 32 + 8 * q + 4 * (l >> 5)) = v;
     }
   }
 }
