@@ -7,6 +7,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <chrono>
 #include <vector>
 
 #include "../../include/specasr.h"
@@ -30,7 +31,7 @@ struct Staging {
 // offsets (in bytes) of the regions of a workspace sized for `rows_max` rows / `batch` sequences
 struct WsLayout {
   size_t meta, outs, rope, x, h, q, k, v, att, gu, t, logits, total;
-  size_t hb, attb, tb, part, blk_val, blk_idx;  // bf16 activations and split-k partial sums (MFMA path)
+  size_t hb, attb, tb, part, ssq, blk_val, blk_idx;  // bf16 activations and split-k partial sums (MFMA path)
   size_t qb, attn_o, attn_ml;                   // MFMA attention: bf16 queries, per-chunk partial outputs
   size_t meta_words;
 };
@@ -154,6 +155,7 @@ WsLayout ws_layout(const specasr_ctx *ctx, int batch) {
   L.attb = take(2 * 64 * dq * 2);
   L.tb = take(2 * 64 * (size_t)c.d_ffn * 2);
   L.part = take((R < 64 ? R : 64) * ctx->part_floats * 4);
+  L.ssq = take(64 * (size_t)residual_slabs(c.d_model) * 4);
   const size_t nblk = (size_t)logits_argmax_blocks(c.vocab);
   L.blk_val = take(R * nblk * 4);
   L.blk_idx = take(R * nblk * 4);
@@ -387,7 +389,8 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
   const int dq = md.n_heads * md.head_dim;
   const int nb = R <= 32 ? 1 : 2;
   float *x = (float *)(ws + L.x), *q = (float *)(ws + L.q), *att = (float *)(ws + L.att);
-  float *part = (float *)(ws + L.part);
+  float *part = (float *)(ws + L.part), *ssq = (float *)(ws + L.ssq);
+  const RowNorm nrm{ssq, residual_slabs(d), d, md.rms_eps};
   uint16_t *hb = (uint16_t *)(ws + L.hb), *attb = (uint16_t *)(ws + L.attb), *tb = (uint16_t *)(ws + L.tb);
   // lo planes follow the hi planes: one plane holds k * 32 * nb elements
   uint16_t *hb_lo = hb + (size_t)d * 32 * nb, *attb_lo = attb + (size_t)dq * 32 * nb, *tb_lo = tb + (size_t)F * 32 * nb;
@@ -430,28 +433,28 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
     const bool pl = l == prof_layer;
     const specasr_layer_weights &lw = ctx->layers[l];
     const PackedLayer &pk = ctx->packed[l];
-    launch_residual_norm(x, part, pending, R, pending_ld, lw.attn_norm, d, md.rms_eps, hb, hb_lo, st);
+    launch_residual_gain(x, part, pending, R, pending_ld, lw.attn_norm, d, hb, hb_lo, ssq, st);
     gemm_stage(ctx, SPECASR_STAGE_QKV, pl, pk.qkv, hb, R, part, pl_qkv, st);
     if (mfma_attn) {
-      launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, ctx->col_k, ctx->col_v, cs, nullptr, qb, qb_lo, kv->k, kv->v, st);
+      launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, nrm, ctx->col_k, ctx->col_v, cs, nullptr, qb, qb_lo, kv->k, kv->v, st);
       launch_tree_attention(m, md, g, l, hs.max_total_keys, hs.max_seq_nodes, qb, qb_lo, kv->k, kv->v,
                             (float *)(ws + L.attn_o), (float *)(ws + L.attn_ml), attb, attb_lo, st);
     } else {
-      launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, ctx->col_k, ctx->col_v, cs, q, nullptr, nullptr, kv->k, kv->v, st);
+      launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, nrm, ctx->col_k, ctx->col_v, cs, q, nullptr, nullptr, kv->k, kv->v, st);
       launch_attention_generic(m, md, g, l, q, kv->k, kv->v, att, st);
       launch_to_bf16(att, R, dq, attb, attb_lo, st);
     }
     gemm_stage(ctx, SPECASR_STAGE_O, pl, pk.o, attb, R, part, pl_o, st);
-    launch_residual_norm(x, part, pl_o.n_splits, R, pk.o.ldo, lw.ffn_norm, d, md.rms_eps, hb, hb_lo, st);
+    launch_residual_gain(x, part, pl_o.n_splits, R, pk.o.ldo, lw.ffn_norm, d, hb, hb_lo, ssq, st);
     gemm_stage(ctx, SPECASR_STAGE_GATE_UP, pl, pk.gu, hb, R, part, pl_gu, st);
-    launch_swiglu_finish(part, pl_gu.n_splits, R, pk.gu.ldo, ctx->col_up, F, tb, tb_lo, st);
+    launch_swiglu_finish(part, pl_gu.n_splits, R, pk.gu.ldo, nrm, ctx->col_up, F, tb, tb_lo, st);
     gemm_stage(ctx, SPECASR_STAGE_DOWN, pl, pk.down, tb, R, part, pl_dn, st);
     pending = pl_dn.n_splits;
     pending_ld = pk.down.ldo;
   }
-  launch_residual_norm(x, part, pending, R, pending_ld, ctx->w.final_norm, d, md.rms_eps, hb, hb_lo, st);
+  launch_residual_gain(x, part, pending, R, pending_ld, ctx->w.final_norm, d, hb, hb_lo, ssq, st);
   gemm_stage(ctx, SPECASR_STAGE_LM_HEAD, true, ctx->lm_head, hb, R, part, pl_lm, st);
-  launch_logits_argmax(m, part, pl_lm.n_splits, ctx->lm_head.ldo, V, ctx->cfg.max_nodes, logits_dev,
+  launch_logits_argmax(m, part, pl_lm.n_splits, ctx->lm_head.ldo, nrm, V, ctx->cfg.max_nodes, logits_dev,
                        (float *)(ws + L.blk_val), (int *)(ws + L.blk_idx), argmax_dev, st);
 }
 
@@ -798,6 +801,8 @@ specasr_status specasr_verify_tree(specasr_ctx *ctx, specasr_kv *kv, const speca
   hipStream_t st = (hipStream_t)stream;
   char *ws = (char *)workspace;
   const WsLayout L = ws_layout(ctx, B);
+  static const bool debug_timing = getenv("SPECASR_DEBUG") != nullptr;
+  const auto t_begin = std::chrono::steady_clock::now();
   HostStep hs;
   build_step(ctx, tree, B, kv->kv_len, &hs);
   s = upload_meta(ctx, hs, ws, L, st);
@@ -814,7 +819,14 @@ specasr_status specasr_verify_tree(specasr_ctx *ctx, specasr_kv *kv, const speca
   HIP_TRY(ctx, hipGetLastError());
   const size_t words = 2 * BN + 2 * (size_t)B;
   HIP_TRY(ctx, hipMemcpyAsync(ctx->out_host, o, words * 4, hipMemcpyDeviceToHost, st));
+  const auto t_enqueued = std::chrono::steady_clock::now();
   HIP_TRY(ctx, hipStreamSynchronize(st));
+  if (debug_timing) {  // host time spent enqueueing the step vs waiting for the GPU to finish it
+    const auto t_done = std::chrono::steady_clock::now();
+    fprintf(stderr, "[specasr] verify_tree: enqueue %.1f us, wait %.1f us\n",
+            std::chrono::duration<double, std::micro>(t_enqueued - t_begin).count(),
+            std::chrono::duration<double, std::micro>(t_done - t_enqueued).count());
+  }
   const int32_t *h = ctx->out_host;
   for (int b = 0; b < B; ++b) {
     const int n = tree->n_nodes[b];

@@ -24,19 +24,27 @@ hipError_t gemm_skinny_set_lds_limit();
 void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *Xp, int rows, float *part,
                         const GemmPlan &plan, int stage, hipStream_t st,
                         hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
-void launch_residual_norm(float *x, const float *part, int n_splits, int rows, int ldp,
-                          const void *gain, int d, float eps, uint16_t *hb, uint16_t *hb_lo,
+// Per-row RMSNorm statistics left by launch_residual_gain for the consumer of the next GEMM.
+struct RowNorm {
+  const float *ssq;  // [rows][n_slab] sums of squares of the residual row, one per column slab
+  int n_slab;
+  int d;      // row length
+  float eps;  // added to the mean square inside the root
+};
+int residual_slabs(int d);
+void launch_residual_gain(float *x, const float *part, int n_splits, int rows, int ldp,
+                          const void *gain, int d, uint16_t *hb, uint16_t *hb_lo, float *ssq,
                           hipStream_t st);
 void launch_qkv_finish(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
-                       const float *part, int n_splits, int ldp, int col_k, int col_v,
-                       const float2 *cs, float *q, uint16_t *qb, uint16_t *qb_lo, void *kc, void *vc,
-                       hipStream_t st);
-void launch_swiglu_finish(const float *part, int n_splits, int rows, int ldp, int col_up, int F,
-                          uint16_t *t, uint16_t *t_lo, hipStream_t st);
+                       const float *part, int n_splits, int ldp, const RowNorm &nrm, int col_k,
+                       int col_v, const float2 *cs, float *q, uint16_t *qb, uint16_t *qb_lo, void *kc,
+                       void *vc, hipStream_t st);
+void launch_swiglu_finish(const float *part, int n_splits, int rows, int ldp, const RowNorm &nrm,
+                          int col_up, int F, uint16_t *t, uint16_t *t_lo, hipStream_t st);
 void launch_to_bf16(const float *src, int rows, int K, uint16_t *dst, uint16_t *dst_lo, hipStream_t st);
 int logits_argmax_blocks(int V);
-void launch_logits_argmax(const StepMeta &m, const float *part, int n_splits, int ldp, int V,
-                          int max_nodes, float *logits_out, float *blk_val, int *blk_idx,
+void launch_logits_argmax(const StepMeta &m, const float *part, int n_splits, int ldp,
+                          const RowNorm &nrm, int V, int max_nodes, float *logits_out, float *blk_val, int *blk_idx,
                           int32_t *argmax, hipStream_t st);
 
 // tree-masked MFMA attention (kernels_attn.hip)

@@ -204,18 +204,25 @@ hipError_t gemm_skinny_set_lds_limit() {
 }
 
 // --------------------------------------------------------------------------- consumers of partial sums
-// x[r][:] += sum_s part[s][r][:]   (n_splits may be 0: plain norm)
-// hb[r][:]  = bf16( x[r][:] * rsqrt(mean(x^2) + eps) * gain )
-__global__ __launch_bounds__(1024) void residual_norm_kernel(float *x, const float *part, int n_splits,
-                                                             int rows, int ldp, const uint16_t *gain,
-                                                             int d, float eps, uint16_t *hb,
-                                                             uint16_t *hb_lo, int nb) {
-  __shared__ float red[16];
-  const int r = blockIdx.x;
-  float *xr = x + (int64_t)r * d;
-  float ss = 0.f;
-  for (int c = threadIdx.x * 4; c < d; c += 4096) {
-    float4 v = *reinterpret_cast<const float4 *>(xr + c);
+// RMSNorm is applied in two halves so that no kernel has to see a whole row: this kernel adds the
+// pending partial sums to the residual stream, multiplies by the norm's gain and records the sum
+// of squares of its 32-column slab; the consumer of the following GEMM multiplies that GEMM's
+// output by 1/rms(row) (the GEMM is linear in its input, so W (g * x / rms) = (W (g * x)) / rms).
+//   x[r][:]   += sum_s part[s][r][:]            (n_splits may be 0)
+//   hb[r][:]   = hi/lo bf16 planes of x[r][:] * gain[:]
+//   ssq[r][slab] = sum over the slab of x[r][c]^2
+// Block = 8 threads per row (4 columns each), grid = slabs of 32 columns.
+constexpr int kSlabCols = 32;
+__global__ __launch_bounds__(512) void residual_gain_kernel(float *x, const float *part, int n_splits,
+                                                            int rows, int ldp, const uint16_t *gain,
+                                                            int d, uint16_t *hb, uint16_t *hb_lo,
+                                                            int nb, float *ssq, int n_slab) {
+  const int r = threadIdx.x >> 3, c = blockIdx.x * kSlabCols + (threadIdx.x & 7) * 4;
+  const bool ok = r < rows && c < d;
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (ok) {
+    float *xr = x + (int64_t)r * d + c;
+    v = *reinterpret_cast<const float4 *>(xr);
     const float *pp = part + (int64_t)r * ldp + c;
     const int64_t sstride = (int64_t)rows * ldp;
     int s = 0;
@@ -233,16 +240,17 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(float *x, const flo
       const float4 p = *reinterpret_cast<const float4 *>(pp + s * sstride);
       v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
     }
-    if (n_splits > 0) *reinterpret_cast<float4 *>(xr + c) = v;
-    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    if (n_splits > 0) *reinterpret_cast<float4 *>(xr) = v;
   }
-  ss = block_sum(ss, red);
-  const float rs = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int c = threadIdx.x * 4; c < d; c += 4096) {
-    const float4 v = *reinterpret_cast<const float4 *>(xr + c);
+  float ss = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  ss += __shfl_xor(ss, 1, 64);
+  ss += __shfl_xor(ss, 2, 64);
+  ss += __shfl_xor(ss, 4, 64);
+  if (ok) {
+    if ((threadIdx.x & 7) == 0) ssq[(int64_t)r * n_slab + blockIdx.x] = ss;
     const uint2 g = *reinterpret_cast<const uint2 *>(gain + c);
-    const float y[4] = {v.x * rs * bf16_bits_to_f32(g.x & 0xffffu), v.y * rs * bf16_bits_to_f32(g.x >> 16),
-                        v.z * rs * bf16_bits_to_f32(g.y & 0xffffu), v.w * rs * bf16_bits_to_f32(g.y >> 16)};
+    const float y[4] = {v.x * bf16_bits_to_f32(g.x & 0xffffu), v.y * bf16_bits_to_f32(g.x >> 16),
+                        v.z * bf16_bits_to_f32(g.y & 0xffffu), v.w * bf16_bits_to_f32(g.y >> 16)};
     uint16_t hi[4], lo[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) split_bf16(y[i], hi[i], lo[i]);
@@ -254,10 +262,22 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(float *x, const flo
   }
 }
 
-void launch_residual_norm(float *x, const float *part, int n_splits, int rows, int ldp,
-                          const void *gain, int d, float eps, uint16_t *hb, uint16_t *hb_lo,
+int residual_slabs(int d) { return (d + kSlabCols - 1) / kSlabCols; }
+
+void launch_residual_gain(float *x, const float *part, int n_splits, int rows, int ldp,
+                          const void *gain, int d, uint16_t *hb, uint16_t *hb_lo, float *ssq,
                           hipStream_t st) {
-  residual_norm_kernel<<<rows, 1024, 0, st>>>(x, part, n_splits, rows, ldp, (const uint16_t *)gain, d, eps, hb, hb_lo, rows <= 32 ? 1 : 2);
+  const int n_slab = residual_slabs(d);
+  residual_gain_kernel<<<n_slab, ((rows + 7) / 8) * 64, 0, st>>>(x, part, n_splits, rows, ldp, (const uint16_t *)gain, d, hb, hb_lo, rows <= 32 ? 1 : 2, ssq, n_slab);
+}
+
+// 1 / rms of residual row r from the slab sums of squares (eps inside the root, Sec. II-A's decoder
+// block).  Every lane of the calling wavefront must be active; all lanes get the same value.
+__device__ __forceinline__ float row_rms_scale(const RowNorm &nrm, int r) {
+  float s = 0.f;
+  for (int i = threadIdx.x & 63; i < nrm.n_slab; i += 64) s += nrm.ssq[(int64_t)r * nrm.n_slab + i];
+  s = wave_sum(s);
+  return 1.0f / sqrtf(s / (float)nrm.d + nrm.eps);
 }
 
 // q, k, v = sum of partials; rotary embedding at the node's depth position (Sec. II-B: each
@@ -266,12 +286,13 @@ void launch_residual_norm(float *x, const float *part, int n_splits, int rows, i
 // attention); k, v -> bf16 cache slot kv_len + node.  Packed columns: [q | pad | k | pad | v].
 __global__ __launch_bounds__(256) void qkv_finish_kernel(StepMeta m, KvGeom g, int layer, int H, int Hkv,
                                                          int hd, const float *part, int n_splits,
-                                                         int ldp, int col_k, int col_v,
+                                                         int ldp, RowNorm nrm, int col_k, int col_v,
                                                          const float2 *cs, float *q, uint16_t *qb,
                                                          uint16_t *qb_lo, float qscale, uint16_t *kc,
                                                          uint16_t *vc) {
   const int r = blockIdx.y, half = hd / 2, rows = m.rows;
   const int idx = blockIdx.x * 256 + threadIdx.x;
+  const float rs = row_rms_scale(nrm, r);
   if (idx >= (H + Hkv) * half) return;
   const int a = idx / half, j = idx - a * half;
   const float2 c = cs[(int64_t)r * half + j];
@@ -286,6 +307,7 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(StepMeta m, KvGeom g, i
       const float v0 = q[c0], v1 = q[c1], v2 = q[c2], v3 = q[c3];
       out[0] += v0; out[1] += v1; out[2] += v2; out[3] += v3;
     }
+    out[0] *= rs; out[1] *= rs; out[2] *= rs; out[3] *= rs;
   };
   if (a < H) {
     float t[4];
@@ -314,20 +336,21 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(StepMeta m, KvGeom g, i
 }
 
 void launch_qkv_finish(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
-                       const float *part, int n_splits, int ldp, int col_k, int col_v,
-                       const float2 *cs, float *q, uint16_t *qb, uint16_t *qb_lo, void *kc, void *vc,
-                       hipStream_t st) {
+                       const float *part, int n_splits, int ldp, const RowNorm &nrm, int col_k,
+                       int col_v, const float2 *cs, float *q, uint16_t *qb, uint16_t *qb_lo, void *kc,
+                       void *vc, hipStream_t st) {
   const int items = (md.n_heads + md.n_kv_heads) * (md.head_dim / 2);
   dim3 grid((items + 255) / 256, m.rows);
-  qkv_finish_kernel<<<grid, 256, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, md.head_dim, part, n_splits, ldp, col_k, col_v, cs, q, qb, qb_lo, 1.0f / sqrtf((float)md.head_dim), (uint16_t *)kc, (uint16_t *)vc);
+  qkv_finish_kernel<<<grid, 256, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, md.head_dim, part, n_splits, ldp, nrm, col_k, col_v, cs, q, qb, qb_lo, 1.0f / sqrtf((float)md.head_dim), (uint16_t *)kc, (uint16_t *)vc);
 }
 
 // t[r][f] = bf16( silu(sum_s gate) * (sum_s up) ); gate at column f, up at column col_up + f
 __global__ __launch_bounds__(256) void swiglu_finish_kernel(const float *part, int n_splits, int rows,
-                                                            int ldp, int col_up, int F, uint16_t *t,
-                                                            uint16_t *t_lo, int nb) {
+                                                            int ldp, RowNorm nrm, int col_up, int F,
+                                                            uint16_t *t, uint16_t *t_lo, int nb) {
   const int r = blockIdx.y;
   const int f = (blockIdx.x * 256 + threadIdx.x) * 4;
+  const float rs = row_rms_scale(nrm, r);
   if (f >= F) return;
   float4 gt = make_float4(0.f, 0.f, 0.f, 0.f), up = gt;
 #pragma unroll 4
@@ -338,7 +361,7 @@ __global__ __launch_bounds__(256) void swiglu_finish_kernel(const float *part, i
     gt.x += a.x; gt.y += a.y; gt.z += a.z; gt.w += a.w;
     up.x += b.x; up.y += b.y; up.z += b.z; up.w += b.w;
   }
-  auto act = [](float gv, float uv) { return gv / (1.0f + __expf(-gv)) * uv; };
+  auto act = [rs](float gv, float uv) { gv *= rs; return gv / (1.0f + __expf(-gv)) * (uv * rs); };
   const float y[4] = {act(gt.x, up.x), act(gt.y, up.y), act(gt.z, up.z), act(gt.w, up.w)};
   uint16_t hi[4], lo[4];
 #pragma unroll
@@ -350,10 +373,10 @@ __global__ __launch_bounds__(256) void swiglu_finish_kernel(const float *part, i
       make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
 }
 
-void launch_swiglu_finish(const float *part, int n_splits, int rows, int ldp, int col_up, int F,
-                          uint16_t *t, uint16_t *t_lo, hipStream_t st) {
+void launch_swiglu_finish(const float *part, int n_splits, int rows, int ldp, const RowNorm &nrm,
+                          int col_up, int F, uint16_t *t, uint16_t *t_lo, hipStream_t st) {
   dim3 grid((F / 4 + 255) / 256, rows);
-  swiglu_finish_kernel<<<grid, 256, 0, st>>>(part, n_splits, rows, ldp, col_up, F, t, t_lo, rows <= 32 ? 1 : 2);
+  swiglu_finish_kernel<<<grid, 256, 0, st>>>(part, n_splits, rows, ldp, nrm, col_up, F, t, t_lo, rows <= 32 ? 1 : 2);
 }
 
 // fp32 -> bf16 row conversion (attention output feeding the output projection)
@@ -381,13 +404,15 @@ void launch_to_bf16(const float *src, int rows, int K, uint16_t *dst, uint16_t *
 // logits[r][v] = sum_s part[s][r][v]; per-(row, block) best (value, lowest index); optional
 // store of the logits into the caller's padded array.  A second tiny kernel merges the blocks.
 __global__ __launch_bounds__(256) void logits_argmax_kernel(StepMeta m, const float *part, int n_splits,
-                                                            int ldp, int V, int max_nodes,
-                                                            float *logits_out, float *blk_val,
+                                                            int ldp, RowNorm nrm, int V,
+                                                            int max_nodes, float *logits_out,
+                                                            float *blk_val,
                                                             int *blk_idx) {
   __shared__ float bv[4];
   __shared__ int bi[4];
   const int r = blockIdx.y, rows = m.rows;
   const int v0 = (blockIdx.x * 256 + threadIdx.x) * 4;
+  const float rs = row_rms_scale(nrm, r);
   float best = -INFINITY;
   int besti = 0x7fffffff;
   if (v0 < V) {
@@ -396,7 +421,7 @@ __global__ __launch_bounds__(256) void logits_argmax_kernel(StepMeta m, const fl
       const float4 p = *reinterpret_cast<const float4 *>(part + ((int64_t)s * rows + r) * ldp + v0);
       a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
     }
-    const float vals[4] = {a.x, a.y, a.z, a.w};
+    const float vals[4] = {a.x * rs, a.y * rs, a.z * rs, a.w * rs};
     if (logits_out) {
       float *dst = logits_out + ((int64_t)m.seq[r] * max_nodes + m.node[r]) * V + v0;
       for (int i = 0; i < 4; ++i)
@@ -443,12 +468,12 @@ __global__ __launch_bounds__(64) void argmax_merge_kernel(StepMeta m, const floa
 
 int logits_argmax_blocks(int V) { return ((V + 3) / 4 + 255) / 256; }
 
-void launch_logits_argmax(const StepMeta &m, const float *part, int n_splits, int ldp, int V,
-                          int max_nodes, float *logits_out, float *blk_val, int *blk_idx,
+void launch_logits_argmax(const StepMeta &m, const float *part, int n_splits, int ldp,
+                          const RowNorm &nrm, int V, int max_nodes, float *logits_out, float *blk_val, int *blk_idx,
                           int32_t *argmax, hipStream_t st) {
   const int n_blk = logits_argmax_blocks(V);
   dim3 grid(n_blk, m.rows);
-  logits_argmax_kernel<<<grid, 256, 0, st>>>(m, part, n_splits, ldp, V, max_nodes, logits_out, blk_val, blk_idx);
+  logits_argmax_kernel<<<grid, 256, 0, st>>>(m, part, n_splits, ldp, nrm, V, max_nodes, logits_out, blk_val, blk_idx);
   argmax_merge_kernel<<<m.rows, 64, 0, st>>>(m, blk_val, blk_idx, n_blk, max_nodes, argmax);
 }
 
