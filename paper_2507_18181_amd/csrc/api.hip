@@ -154,7 +154,7 @@ WsLayout ws_layout(const specasr_ctx *ctx, int batch) {
   L.hb = take(2 * 64 * (size_t)c.d_model * 2);
   L.attb = take(2 * 64 * dq * 2);
   L.tb = take(2 * 64 * (size_t)c.d_ffn * 2);
-  L.part = take((R < 64 ? R : 64) * ctx->part_floats * 4);
+  L.part = take(64 * ctx->part_floats * 4);  // [split][band][rows padded to 32 or 64][32]
   L.ssq = take(64 * (size_t)residual_slabs(c.d_model) * 4);
   const size_t nblk = (size_t)logits_argmax_blocks(c.vocab);
   L.blk_val = take(R * nblk * 4);

@@ -44,6 +44,15 @@ __host__ __device__ __forceinline__ int64_t packed_act_offset(int row, int col, 
   return ((((int64_t)(col >> 4) * nb + (row >> 5)) * 64 + (row & 31) + 32 * ((col >> 3) & 1)) << 3) + (col & 7);
 }
 
+// Element offset of split-k partial sum (split s, activation row, output column) in the partial-sum
+// buffer: [split][band = col/32][row, padded to rows_pad = 32 or 64][col%32].  One (split, band)
+// block is contiguous, so the GEMM writes it with full-line stores and a consumer thread reads
+// 4 consecutive columns as one float4 (col a multiple of 4).
+__host__ __device__ __forceinline__ int64_t part_offset(int s, int row, int col, int n_bands, int rows_pad) {
+  return ((((int64_t)s * n_bands + (col >> 5)) * rows_pad + row) << 5) + (col & 31);
+}
+__host__ __device__ __forceinline__ int part_rows_pad(int rows) { return rows <= 32 ? 32 : 64; }
+
 // ---- per-call tree metadata as the kernels see it ------------------------
 // Rows are the tree nodes of all sequences of the call, flattened without
 // padding: row = row_start[seq] + node.

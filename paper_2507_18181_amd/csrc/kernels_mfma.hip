@@ -25,6 +25,7 @@
 
 #include "kernels.h"
 #include "kernels_mfma.h"
+#include <type_traits>
 
 namespace specasr {
 
@@ -56,17 +57,22 @@ void launch_repack(const void *src, int n_out, int K, void *dst, int band0, hipS
 }
 
 // --------------------------------------------------------------------------- skinny GEMM
-// part[s][row][o] = sum over k in chunk s of X[row][k] * W[o][k]
+// part[s][band][row][o % 32] = sum over k in chunk s of X[row][k] * W[o][k]   (see part_offset)
 // grid.x = P (a multiple of S), block = 512.  Workgroup g: chunk s = g % S, bands g/S + j*(P/S).
-// Xp: packed activations [plane hi|lo][kstep][NB][64 lanes] x 16 bytes.  LDS: 2 x 8 x NB x 4 KB.
+// Xp: packed activations [plane hi|lo][kstep][NB][64 lanes] x 16 bytes.
 // STAGE only names the projection (0 qkv, 1 o, 2 gate|up, 3 down, 4 LM head) so that a profiler
 // lists each of them as its own kernel; the code is identical.
+constexpr int kRedStride = 66;                  // floats between accumulator registers in LDS
+constexpr int kRedFloats = 16 * kRedStride;     // one wavefront's 32x32 tile
+template <int NB>
+constexpr size_t gemm_lds_bytes() { return (size_t)2 * 8 * NB * kRedFloats * 4; }
+
 template <int NB, int LW, int STAGE>
 __global__ __launch_bounds__(512) void gemm_skinny_kernel(const u32x4 *__restrict__ Wp,
                                                           const u32x4 *__restrict__ Xp,
-                                                          float *__restrict__ part, int ldo,
+                                                          float *__restrict__ part,
                                                           int rows, int n_bands, int ksteps, int S) {
-  extern __shared__ float red[];  // [2][8][NB * 1024]
+  extern __shared__ float red[];  // [2][8 wavefronts][NB][kRedFloats]
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int P = gridDim.x;
   const int s = blockIdx.x % S, bg = blockIdx.x / S, bstride = P / S;
@@ -101,11 +107,14 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(const u32x4 *__restric
       xh[k][n] = ok ? Xp[off] : (u32x4){0u, 0u, 0u, 0u};
       xl[k][n] = ok ? Xp[plane + off] : (u32x4){0u, 0u, 0u, 0u};
     }
+  const int rows_pad = NB * 32;
 
-  for (int unit = 0; unit < n_units; ++unit) {
+  // One band: multiply the ring with the activations while (refill) slot k is reloaded with the
+  // same tile of the next band, then sum the 8 wavefronts' tiles through LDS and store the block.
+  // The last band is a copy of the code without the reloads, so the steady state has no branch.
+  auto do_band = [&](int unit, auto refill) {
     const int band = bg + unit * bstride;
-    const int nband = unit + 1 < n_units ? band + bstride : band;  // the last band is re-read, unused
-    const u32x4 *pn = wbase + (int64_t)nband * band_stride;
+    const u32x4 *pn = wbase + (int64_t)(band + bstride) * band_stride;
     f32x16 acc[NB][2];
 #pragma unroll
     for (int n = 0; n < NB; ++n)
@@ -121,41 +130,46 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(const u32x4 *__restric
         acc[n][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, xh[k][n]), acc[n][0], 0, 0, 0);
         acc[n][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, xl[k][n]), acc[n][1], 0, 0, 0);
       }
-      buf[k] = load_stream(pn + toff[k]);  // same tile of the next band
+      if (decltype(refill)::value) buf[k] = load_stream(pn + toff[k]);
     }
-    // sum the 8 slices: C layout = node column l%32, output rows 8*(j/4) + 4*(l/32) + j%4
-    float *mine = red + ((unit & 1) * 8 + wave) * (NB * 1024);
+    // C layout: register j of lane l = node column l%32, output row 8*(j/4) + 4*(l/32) + j%4
+    float *mine = red + ((unit & 1) * 8 + wave) * (NB * kRedFloats);
 #pragma unroll
     for (int n = 0; n < NB; ++n)
 #pragma unroll
-      for (int j = 0; j < 16; ++j) mine[n * 1024 + j * 64 + lane] = acc[n][0][j] + acc[n][1][j];
+      for (int j = 0; j < 16; ++j) mine[n * kRedFloats + j * kRedStride + lane] = acc[n][0][j] + acc[n][1][j];
     __syncthreads();
-    const float *all = red + (unit & 1) * 8 * (NB * 1024);
-    // thread (n, q, l) sums output rows 8q + 4*(l/32) + 0..3 of node n*32 + l%32: one 16-byte store
+    const float *all = red + (unit & 1) * 8 * (NB * kRedFloats);
+    // thread (node, seg) sums output rows 4*seg .. 4*seg+3 of its node over the 8 wavefronts; the
+    // 256 threads of a node group write one contiguous 4 KB block [node][32 outputs]
     if ((int)threadIdx.x < NB * 256) {
-      const int n = threadIdx.x >> 8, q = (threadIdx.x >> 6) & 3, l = threadIdx.x & 63;
+      const int n = threadIdx.x >> 8, node = (threadIdx.x >> 3) & 31, seg = threadIdx.x & 7;
+      const int q = seg >> 1, h = seg & 1;
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
       for (int w = 0; w < 8; ++w) {
-        const float *src = all + w * (NB * 1024) + n * 1024 + (4 * q) * 64 + l;
-        v.x += src[0]; v.y += src[64]; v.z += src[128]; v.w += src[192];
+        const float *src = all + w * (NB * kRedFloats) + n * kRedFloats + (4 * q) * kRedStride + node + 32 * h;
+        v.x += src[0]; v.y += src[kRedStride]; v.z += src[2 * kRedStride]; v.w += src[3 * kRedStride];
       }
-      const int node = n * 32 + (l & 31);
-      if (node < rows)
-        *reinterpret_cast<float4 *>(part + ((int64_t)s * rows + node) * ldo + band * 32 + 8 * q + 4 * (l >> 5)) = v;
+      const int row = n * 32 + node;
+      if (row < rows)
+        *reinterpret_cast<float4 *>(part + part_offset(s, row, band * 32 + seg * 4, n_bands, rows_pad)) = v;
     }
-  }
+  };
+  int unit = 0;
+  for (; unit + 1 < n_units; ++unit) do_band(unit, std::true_type{});
+  do_band(unit, std::false_type{});
 }
 
 template <int NB, int LW, int STAGE>
 static void launch_gemm_t(const PackedMatrix &W, const uint16_t *Xp, int rows, float *part,
                           const GemmPlan &plan, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
-  const size_t lds = (size_t)2 * 8 * NB * 4096;
+  const size_t lds = gemm_lds_bytes<NB>();
   if (ev0 != nullptr)  // the events take the start and stop time of this dispatch itself
     hipExtLaunchKernelGGL((gemm_skinny_kernel<NB, LW, STAGE>), dim3(plan.grid), dim3(512), (uint32_t)lds, st, ev0, ev1, 0u,
-                          (const u32x4 *)W.data, (const u32x4 *)Xp, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits);
+                          (const u32x4 *)W.data, (const u32x4 *)Xp, part, rows, W.n_bands, W.ksteps, plan.n_splits);
   else
-    gemm_skinny_kernel<NB, LW, STAGE><<<plan.grid, 512, lds, st>>>((const u32x4 *)W.data, (const u32x4 *)Xp, part, W.ldo, rows, W.n_bands, W.ksteps, plan.n_splits);
+    gemm_skinny_kernel<NB, LW, STAGE><<<plan.grid, 512, lds, st>>>((const u32x4 *)W.data, (const u32x4 *)Xp, part, rows, W.n_bands, W.ksteps, plan.n_splits);
 }
 
 template <int STAGE>
@@ -186,12 +200,20 @@ void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *Xp, int rows, flo
   }
 }
 
+template <int NB, int LW, int STAGE>
+static hipError_t set_lds_t() {
+  return hipFuncSetAttribute((const void *)gemm_skinny_kernel<NB, LW, STAGE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes<NB>());
+}
+
 template <int STAGE>
 static hipError_t set_lds_s() {
-  const int big = 2 * 8 * 2 * 4096;
-  hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<2, 4, STAGE>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute((const void *)gemm_skinny_kernel<2, 8, STAGE>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
+  hipError_t e = set_lds_t<1, 4, STAGE>();
+  if (e == hipSuccess) e = set_lds_t<1, 8, STAGE>();
+  if (e == hipSuccess) e = set_lds_t<1, 12, STAGE>();
+  if (e == hipSuccess) e = set_lds_t<1, 16, STAGE>();
+  if (e == hipSuccess) e = set_lds_t<2, 4, STAGE>();
+  if (e == hipSuccess) e = set_lds_t<2, 8, STAGE>();
+  return e;
 }
 
 hipError_t gemm_skinny_set_lds_limit() {
@@ -223,8 +245,9 @@ __global__ __launch_bounds__(512) void residual_gain_kernel(float *x, const floa
   if (ok) {
     float *xr = x + (int64_t)r * d + c;
     v = *reinterpret_cast<const float4 *>(xr);
-    const float *pp = part + (int64_t)r * ldp + c;
-    const int64_t sstride = (int64_t)rows * ldp;
+    const int rows_pad = part_rows_pad(rows);
+    const float *pp = part + part_offset(0, r, c, ldp >> 5, rows_pad);
+    const int64_t sstride = (int64_t)ldp * rows_pad;
     int s = 0;
     for (; s + 4 <= n_splits; s += 4) {  // four independent loads in flight, summed in split order
       const float4 p0 = *reinterpret_cast<const float4 *>(pp + (s + 0) * sstride);
@@ -296,15 +319,17 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(StepMeta m, KvGeom g, i
   if (idx >= (H + Hkv) * half) return;
   const int a = idx / half, j = idx - a * half;
   const float2 c = cs[(int64_t)r * half + j];
-  const float *pr = part + (int64_t)r * ldp;
-  const int64_t sstride = (int64_t)rows * ldp;
+  const int rows_pad = part_rows_pad(rows);
+  const float *pr = part + part_offset(0, r, 0, ldp >> 5, rows_pad);  // column c at (c/32)*rows_pad*32 + c%32
+  const int64_t sstride = (int64_t)ldp * rows_pad;
+  auto at = [rows_pad](int col) { return (col >> 5) * (rows_pad << 5) + (col & 31); };
   // sums of the split-k partials of up to four columns, loads of one split issued together
   auto val4 = [&](int c0, int c1, int c2, int c3, float (&out)[4]) {
     out[0] = out[1] = out[2] = out[3] = 0.f;
 #pragma unroll 4
     for (int s = 0; s < n_splits; ++s) {
       const float *q = pr + s * sstride;
-      const float v0 = q[c0], v1 = q[c1], v2 = q[c2], v3 = q[c3];
+      const float v0 = q[at(c0)], v1 = q[at(c1)], v2 = q[at(c2)], v3 = q[at(c3)];
       out[0] += v0; out[1] += v1; out[2] += v2; out[3] += v3;
     }
     out[0] *= rs; out[1] *= rs; out[2] *= rs; out[3] *= rs;
@@ -353,11 +378,11 @@ __global__ __launch_bounds__(256) void swiglu_finish_kernel(const float *part, i
   const float rs = row_rms_scale(nrm, r);
   if (f >= F) return;
   float4 gt = make_float4(0.f, 0.f, 0.f, 0.f), up = gt;
+  const int rows_pad = part_rows_pad(rows), n_bands = ldp >> 5;
 #pragma unroll 4
   for (int s = 0; s < n_splits; ++s) {
-    const float *p = part + ((int64_t)s * rows + r) * ldp;
-    const float4 a = *reinterpret_cast<const float4 *>(p + f);
-    const float4 b = *reinterpret_cast<const float4 *>(p + col_up + f);
+    const float4 a = *reinterpret_cast<const float4 *>(part + part_offset(s, r, f, n_bands, rows_pad));
+    const float4 b = *reinterpret_cast<const float4 *>(part + part_offset(s, r, col_up + f, n_bands, rows_pad));
     gt.x += a.x; gt.y += a.y; gt.z += a.z; gt.w += a.w;
     up.x += b.x; up.y += b.y; up.z += b.z; up.w += b.w;
   }
@@ -418,7 +443,7 @@ __global__ __launch_bounds__(256) void logits_argmax_kernel(StepMeta m, const fl
   if (v0 < V) {
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int s = 0; s < n_splits; ++s) {
-      const float4 p = *reinterpret_cast<const float4 *>(part + ((int64_t)s * rows + r) * ldp + v0);
+      const float4 p = *reinterpret_cast<const float4 *>(part + part_offset(s, r, v0, ldp >> 5, part_rows_pad(rows)));
       a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
     }
     const float vals[4] = {a.x * rs, a.y * rs, a.z * rs, a.w * rs};
