@@ -263,6 +263,9 @@ StepMeta device_meta(const specasr_ctx *ctx, char *ws, const WsLayout &L, int ba
   m.n_nodes = m.row_start + batch_cap;
   m.rows = hs.rows;
   m.batch = hs.batch;
+  const size_t R_host = (size_t)hs.batch * ctx->cfg.max_nodes;  // layout of hs.words
+  m.kv_len0 = hs.words[10 * R_host];
+  m.n_nodes0 = hs.words[10 * R_host + 2 * (size_t)hs.batch];
   return m;
 }
 

@@ -70,6 +70,13 @@ struct StepMeta {
   const int32_t *row_start;  // [batch]
   const int32_t *n_nodes;    // [batch]
   int32_t rows, batch;
+  // Copies of kv_len[0] and n_nodes[0] that travel with the kernel arguments: a single-sequence
+  // call (the common case) needs no dependent global load to find its key range.
+  int32_t kv_len0, n_nodes0;
+  __device__ __forceinline__ int seq_of_row(int r) const { return batch == 1 ? 0 : seq[r]; }
+  __device__ __forceinline__ int seq_kv_len(int s) const { return batch == 1 ? kv_len0 : kv_len[s]; }
+  __device__ __forceinline__ int seq_n_nodes(int s) const { return batch == 1 ? n_nodes0 : n_nodes[s]; }
+  __device__ __forceinline__ int seq_row_start(int s) const { return batch == 1 ? 0 : row_start[s]; }
 };
 
 // KV cache geometry: element index of (seq, layer, kv head, slot, 0)

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256) void tree_attention_kernel(StepMeta m, KvGeom 
   const int lane = threadIdx.x & 63, h = lane >> 5, ql = lane & 31;
   const int chunk = blockIdx.x, kvh = blockIdx.y / n_rgb, rgb = blockIdx.y % n_rgb, seq = blockIdx.z;
   const int G = H / Hkv;
-  const int L = m.kv_len[seq], n = m.n_nodes[seq], r0 = m.row_start[seq], rows = m.rows;
+  const int L = m.seq_kv_len(seq), n = m.seq_n_nodes(seq), r0 = m.seq_row_start(seq), rows = m.rows;
   const int T = L + n, QR = G * n;
   const int t_begin = chunk * chunk_keys;
   if (t_begin >= T || rgb * RGW * 32 >= QR) return;
@@ -283,8 +283,8 @@ __global__ void tree_attention_merge_kernel(StepMeta m, int H, int HD, int chunk
                                             uint16_t *__restrict__ out, uint16_t *__restrict__ out_lo,
                                             int nb) {
   const int a = blockIdx.x, r = blockIdx.y, c = threadIdx.x, rows = m.rows;
-  const int seq = m.seq[r];
-  const int T = m.kv_len[seq] + m.n_nodes[seq];
+  const int seq = m.seq_of_row(r);
+  const int T = m.seq_kv_len(seq) + m.seq_n_nodes(seq);
   const int n_chunks = (T + chunk_keys - 1) / chunk_keys;
   // batches of 8 chunks with all loads issued together; running (max, numerator, denominator)
   float M = -INFINITY, num = 0.f, den = 0.f;
