@@ -187,9 +187,10 @@ specasr_status specasr_commit(specasr_ctx *ctx, specasr_kv *kv, const int32_t *n
                               const int32_t *path, const int32_t *accept_len, void *workspace,
                               size_t workspace_bytes, void *stream);
 
-/* Which kernels a forward over `rows` tree nodes in total would use: 1 = the bf16 MFMA path,
- * 0 = the dtype-generic kernels (fp32 models, SPECASR_FLAG_GENERIC_KERNELS / NO_REPACK, shapes
- * the MFMA tiling does not cover, more than 64 rows). */
+/* Which kernels a forward over `rows` tree nodes in total would use: 1 = the bf16 MFMA path
+ * (a call with more than 64 rows runs as consecutive groups of whole sequences with at most 64
+ * rows each), 0 = the dtype-generic kernels (fp32 models, SPECASR_FLAG_GENERIC_KERNELS /
+ * NO_REPACK, shapes the MFMA tiling does not cover). */
 int32_t specasr_uses_mfma(const specasr_ctx *ctx, int32_t rows);
 
 /* Measurement aid for benchmarks (no effect on results).  While enabled, every forward

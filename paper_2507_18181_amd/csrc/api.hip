@@ -474,6 +474,44 @@ specasr_status forward_common(specasr_ctx *ctx, specasr_kv *kv, const specasr_tr
   return SPECASR_OK;
 }
 
+// A consecutive run of whole sequences of one call, with views of the caller's cache and trees
+// that start at its first sequence.
+struct SeqGroup {
+  int s0 = 0;  // first sequence
+  specasr_kv kv{};
+  specasr_tree tree{};
+};
+
+// The MFMA kernels take at most 64 activation rows, so a call with more tree nodes in total is
+// run as consecutive groups of whole sequences with <= 64 rows each (a tree has <= 64 nodes);
+// the dtype-generic kernels take the whole call at once.
+std::vector<SeqGroup> split_call(const specasr_ctx *ctx, const specasr_kv *kv, const specasr_tree *tree) {
+  const specasr_config &c = ctx->cfg;
+  const size_t esz = c.dtype == SPECASR_BF16 ? 2 : 4;
+  const size_t seq_kv_bytes = (size_t)c.n_layers * c.n_kv_heads * (size_t)kv->capacity * c.head_dim * esz;
+  std::vector<SeqGroup> out;
+  int b = 0;
+  while (b < kv->batch) {
+    int e = b, rows = 0;
+    while (e < kv->batch && (!ctx->fast || rows + tree->n_nodes[e] <= 64)) rows += tree->n_nodes[e++];
+    SeqGroup g;
+    g.s0 = b;
+    g.kv.k = (char *)kv->k + (size_t)b * seq_kv_bytes;
+    g.kv.v = (char *)kv->v + (size_t)b * seq_kv_bytes;
+    g.kv.capacity = kv->capacity;
+    g.kv.batch = e - b;
+    g.kv.kv_len = kv->kv_len + b;
+    g.tree.tokens = tree->tokens + (size_t)b * c.max_nodes;
+    g.tree.parents = tree->parents + (size_t)b * c.max_nodes;
+    g.tree.n_nodes = tree->n_nodes + b;
+    g.tree.input_embeds = tree->input_embeds ? (const char *)tree->input_embeds + (size_t)b * c.max_nodes * c.d_model * esz : nullptr;
+    g.tree.use_embed = tree->use_embed ? tree->use_embed + (size_t)b * c.max_nodes : nullptr;
+    out.push_back(g);
+    b = e;
+  }
+  return out;
+}
+
 // One-time repack of the bf16 weights into MFMA-tile order (values unchanged).  Allocates the
 // packed copies; q|k|v and gate|up are concatenated, each part starting on a 32-row band.
 specasr_status build_packed(specasr_ctx *ctx) {
@@ -567,7 +605,7 @@ const char *specasr_strerror(specasr_status s) {
 int32_t specasr_last_hip_error(const specasr_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
 
 int32_t specasr_uses_mfma(const specasr_ctx *ctx, int32_t rows) {
-  return (ctx && ctx->fast && rows >= 1 && rows <= 64) ? 1 : 0;
+  return (ctx && ctx->fast && rows >= 1) ? 1 : 0;
 }
 
 specasr_status specasr_profile_stage(specasr_ctx *ctx, int32_t stage, int32_t enable) {
@@ -686,11 +724,17 @@ specasr_status specasr_tree_forward(specasr_ctx *ctx, specasr_kv *kv, const spec
   hipStream_t st = (hipStream_t)stream;
   char *ws = (char *)workspace;
   const WsLayout L = ws_layout(ctx, kv->batch);
-  HostStep hs;
-  build_step(ctx, tree, kv->batch, kv->kv_len, &hs);
-  s = upload_meta(ctx, hs, ws, L, st);
-  if (s != SPECASR_OK) return s;
-  return forward_common(ctx, kv, tree, argmax_dev, logits_dev, ws, L, hs, st);
+  const size_t MN = (size_t)ctx->cfg.max_nodes;
+  for (SeqGroup &grp : split_call(ctx, kv, tree)) {
+    HostStep hs;
+    build_step(ctx, &grp.tree, grp.kv.batch, grp.kv.kv_len, &hs);
+    s = upload_meta(ctx, hs, ws, L, st);
+    if (s != SPECASR_OK) return s;
+    s = forward_common(ctx, &grp.kv, &grp.tree, argmax_dev + grp.s0 * MN,
+                       logits_dev ? logits_dev + grp.s0 * MN * ctx->cfg.vocab : nullptr, ws, L, hs, st);
+    if (s != SPECASR_OK) return s;
+  }
+  return SPECASR_OK;
 }
 
 specasr_status specasr_accept(specasr_ctx *ctx, const specasr_tree *tree, int32_t batch,
@@ -806,20 +850,23 @@ specasr_status specasr_verify_tree(specasr_ctx *ctx, specasr_kv *kv, const speca
   const WsLayout L = ws_layout(ctx, B);
   static const bool debug_timing = getenv("SPECASR_DEBUG") != nullptr;
   const auto t_begin = std::chrono::steady_clock::now();
-  HostStep hs;
-  build_step(ctx, tree, B, kv->kv_len, &hs);
-  s = upload_meta(ctx, hs, ws, L, st);
-  if (s != SPECASR_OK) return s;
   int32_t *o = reinterpret_cast<int32_t *>(ws + L.outs);
-  const size_t BN = (size_t)B * c.max_nodes;
+  const size_t BN = (size_t)B * c.max_nodes, MN = (size_t)c.max_nodes;
   int32_t *argmax_dev = o, *path_dev = o + BN, *len_dev = o + 2 * BN, *next_dev = len_dev + B;
-  s = forward_common(ctx, kv, tree, argmax_dev, out->logits, ws, L, hs, st);
-  if (s != SPECASR_OK) return s;
-  StepMeta m = device_meta(ctx, ws, L, B, hs);
-  KvGeom g{kv->capacity, c.n_layers, c.n_kv_heads, c.head_dim};
-  launch_accept(m, c.max_nodes, argmax_dev, path_dev, len_dev, next_dev, st);
-  launch_compact(c.dtype, g, B, c.max_nodes, m.kv_len, path_dev, len_dev, kv->k, kv->v, st);
-  HIP_TRY(ctx, hipGetLastError());
+  for (SeqGroup &grp : split_call(ctx, kv, tree)) {
+    HostStep hs;
+    build_step(ctx, &grp.tree, grp.kv.batch, grp.kv.kv_len, &hs);
+    s = upload_meta(ctx, hs, ws, L, st);
+    if (s != SPECASR_OK) return s;
+    s = forward_common(ctx, &grp.kv, &grp.tree, argmax_dev + grp.s0 * MN,
+                       out->logits ? out->logits + grp.s0 * MN * c.vocab : nullptr, ws, L, hs, st);
+    if (s != SPECASR_OK) return s;
+    StepMeta m = device_meta(ctx, ws, L, grp.kv.batch, hs);
+    KvGeom g{kv->capacity, c.n_layers, c.n_kv_heads, c.head_dim};
+    launch_accept(m, c.max_nodes, argmax_dev + grp.s0 * MN, path_dev + grp.s0 * MN, len_dev + grp.s0, next_dev + grp.s0, st);
+    launch_compact(c.dtype, g, grp.kv.batch, c.max_nodes, m.kv_len, path_dev + grp.s0 * MN, len_dev + grp.s0, grp.kv.k, grp.kv.v, st);
+    HIP_TRY(ctx, hipGetLastError());
+  }
   const size_t words = 2 * BN + 2 * (size_t)B;
   HIP_TRY(ctx, hipMemcpyAsync(ctx->out_host, o, words * 4, hipMemcpyDeviceToHost, st));
   const auto t_enqueued = std::chrono::steady_clock::now();

@@ -140,8 +140,9 @@ def test_cfg2_planted_trunk_and_library_prefill(model_1b):
 
 def test_cfg4_1b_batch16_ragged(model_1b):
     """16 utterances, prefix lengths uniform in [200, 1500], each with its own 24-node tree (trunk 16 +
-    two depth-4 branches): one call; every sequence equals the oracle run on it alone.  More than 64
-    rows in total, so this runs the dtype-generic kernels."""
+    two depth-4 branches): one call; every sequence equals the oracle run on it alone.  384 rows in
+    total: the library runs them as eight groups of two sequences on the MFMA kernels."""
+    from paper_2507_18181_amd import binding as B
     spec = wl.WORKLOADS["cfg4_1b_b16"]
     cfg = model_1b.cfg
     rng = np.random.default_rng([spec["seed"], 1])
@@ -151,6 +152,7 @@ def test_cfg4_1b_batch16_ragged(model_1b):
     ver = model_1b.verifier(cap, max_batch=Bn)
     K, V = wl.seeded_cache(cfg, spec["seed"], Ls, cap, "bf16", batch=Bn)
     ver.set_cache(K, V, Ls)
+    assert B.specasr_uses_mfma(ver.ctx, Bn * 24) == 1
     t = spec["tree"]
     trees, toks = [], []
     for b in range(Bn):

@@ -175,6 +175,47 @@ def test_batch_of_ragged_sequences():
     ver.close()
 
 
+def test_batch_above_64_rows_runs_in_sequence_groups_on_the_mfma_path():
+    """Seven bf16 sequences with 150 tree nodes in total (one full 64-node tree): the call is
+    processed as consecutive groups of whole sequences with at most 64 rows each, all on the MFMA
+    kernels; every sequence equals the oracle run on it alone, and tree_forward agrees."""
+    from paper_2507_18181_amd import binding as B
+    cfg = wl.MODELS["tiny"]
+    w = wl.make_weights(cfg, 91, "bf16")
+    rng = np.random.default_rng(92)
+    sizes = (20, 30, 14, 64, 1, 5, 16)
+    Ls = [37, 90, 5, 60, 0, 33, 64]
+    nb, cap = len(sizes), 160
+    ver = _verifier(cfg, w, "bf16", max_nodes=64, capacity=cap, max_batch=nb)
+    assert B.specasr_uses_mfma(ver.ctx, sum(sizes)) == 1
+    om = oracle.OracleModel(cfg, w)
+    K, V = wl.seeded_cache(cfg, 93, np.asarray(Ls, np.int32), cap, "bf16", batch=nb)
+    ver.set_cache(K, V, Ls)
+    trees = [wl.random_tree(rng, n) for n in sizes]
+    toks = [wl.tree_tokens(rng, p, cfg["vocab"]) for p in trees]
+    fwd = ver.tree_forward(toks, trees, want_logits=True)
+    assert fwd["status"] == 0
+    ver.set_cache(K, V, Ls)                      # tree_forward wrote the tree rows; start again
+    out = ver.verify_tree(toks, trees, want_logits=True)
+    assert out["status"] == 0
+    k2, v2 = ver.get_cache()
+    for b in range(nb):
+        n = sizes[b]
+        ref = om.tree_forward(np.ascontiguousarray(K[b]), np.ascontiguousarray(V[b]), Ls[b], toks[b], trees[b])
+        check_forward(ref, out["logits"][b].cpu().numpy(), out["argmax"][b], TOL_BF16)
+        assert np.array_equal(fwd["argmax"][b, :n].cpu().numpy(), out["argmax"][b, :n])
+        assert torch.equal(fwd["logits"][b, :n], out["logits"][b, :n])
+        path, alen, nxt = oracle.accept(toks[b], trees[b], out["argmax"][b, :n])
+        assert out["accept_len"][b] == alen and out["next_token"][b] == nxt
+        assert out["path"][b, :alen].tolist() == path.tolist()
+        assert ver.kv_len[b] == Ls[b] + alen
+        want = ref["ktree"][:, :, path]
+        got = widen_cache(k2[b, :, :, Ls[b]:Ls[b] + alen])
+        assert np.abs(got - want).max() <= TOL_BF16 * np.abs(want).max()
+        assert np.all(out["argmax"][b, n:] == -1)
+    ver.close()
+
+
 def test_accept_stage_bit_exact_against_oracle():
     """Acceptance from device argmax arrays and from logits, random trees with tiny vocabularies
     (many matches, duplicate sibling tokens), batch of 5, sizes 1..64."""
