@@ -67,8 +67,13 @@ constexpr int kRedFloats = 16 * kRedStride;     // one wavefront's 32x32 tile
 template <int NB>
 constexpr size_t gemm_lds_bytes() { return (size_t)2 * 8 * NB * kRedFloats * 4; }
 
+// Wavefronts 8.. of a workgroup (NR of them; where the register budget allows any) do nothing but
+// the summation and the stores, so the 8 streaming wavefronts never fall behind one another.
+template <int NB, int LW>
+constexpr int gemm_reducers() { return (NB == 1 && LW <= 8) ? 4 : 0; }
+
 template <int NB, int LW, int STAGE>
-__global__ __launch_bounds__(512) void gemm_skinny_kernel(const u32x4 *__restrict__ Wp,
+__global__ __launch_bounds__((512 + 64 * gemm_reducers<NB, LW>())) void gemm_skinny_kernel(const u32x4 *__restrict__ Wp,
                                                           const u32x4 *__restrict__ Xp,
                                                           float *__restrict__ part,
                                                           int rows, int n_bands, int ksteps, int S) {
@@ -82,6 +87,37 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(const u32x4 *__restric
   const int len = w1 - w0;  // 0 <= len <= LW
   const int n_units = bg < n_bands ? (n_bands - bg + bstride - 1) / bstride : 0;
   if (n_units == 0) return;
+  constexpr int NR = gemm_reducers<NB, LW>();
+  const int rows_pad = NB * 32;
+  // thread rt of the summing threads: (node group, node, seg) sums output rows 4*seg .. 4*seg+3 of
+  // its node over the 8 streaming wavefronts; the 256 threads of a node group write one
+  // contiguous 4 KB block [node][32 outputs].  C layout: register j of lane l = node column l%32,
+  // output row 8*(j/4) + 4*(l/32) + j%4.
+  auto sum_and_store = [&](int rt, int unit) {
+    const float *all = red + (unit & 1) * 8 * (NB * kRedFloats);
+    const int band = bg + unit * bstride;
+    const int n = rt >> 8, node = (rt >> 3) & 31, seg = rt & 7;
+    const int q = seg >> 1, h = seg & 1;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int w = 0; w < 8; ++w) {
+      const float *src = all + w * (NB * kRedFloats) + n * kRedFloats + (4 * q) * kRedStride + node + 32 * h;
+      v.x += src[0]; v.y += src[kRedStride]; v.z += src[2 * kRedStride]; v.w += src[3 * kRedStride];
+    }
+    const int row = n * 32 + node;
+    if (row < rows)
+      *reinterpret_cast<float4 *>(part + part_offset(s, row, band * 32 + seg * 4, n_bands, rows_pad)) = v;
+  };
+  if (NR > 0 && wave >= 8) {
+    // One barrier per band on both sides: the streaming wavefronts arrive after writing buffer
+    // unit%2, this side after reading buffer (unit-1)%2 -- which is therefore free again before
+    // band unit+1 is written into it.
+    for (int unit = 0; unit < n_units; ++unit) {
+      __syncthreads();
+      sum_and_store((int)threadIdx.x - 512, unit);
+    }
+    return;
+  }
   const int64_t band_stride = (int64_t)ksteps * 64;
   const u32x4 *wbase = Wp + (int64_t)min(w0, ksteps - 1) * 64 + lane;
   // slot k reads tile min(k, len-1) of the slice (a duplicate beyond the slice: multiplied by zero)
@@ -107,7 +143,6 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(const u32x4 *__restric
       xh[k][n] = ok ? Xp[off] : (u32x4){0u, 0u, 0u, 0u};
       xl[k][n] = ok ? Xp[plane + off] : (u32x4){0u, 0u, 0u, 0u};
     }
-  const int rows_pad = NB * 32;
 
   // One band: multiply the ring with the activations while (refill) slot k is reloaded with the
   // same tile of the next band, then sum the 8 wavefronts' tiles through LDS and store the block.
@@ -132,29 +167,13 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(const u32x4 *__restric
       }
       if (decltype(refill)::value) buf[k] = load_stream(pn + toff[k]);
     }
-    // C layout: register j of lane l = node column l%32, output row 8*(j/4) + 4*(l/32) + j%4
     float *mine = red + ((unit & 1) * 8 + wave) * (NB * kRedFloats);
 #pragma unroll
     for (int n = 0; n < NB; ++n)
 #pragma unroll
       for (int j = 0; j < 16; ++j) mine[n * kRedFloats + j * kRedStride + lane] = acc[n][0][j] + acc[n][1][j];
     __syncthreads();
-    const float *all = red + (unit & 1) * 8 * (NB * kRedFloats);
-    // thread (node, seg) sums output rows 4*seg .. 4*seg+3 of its node over the 8 wavefronts; the
-    // 256 threads of a node group write one contiguous 4 KB block [node][32 outputs]
-    if ((int)threadIdx.x < NB * 256) {
-      const int n = threadIdx.x >> 8, node = (threadIdx.x >> 3) & 31, seg = threadIdx.x & 7;
-      const int q = seg >> 1, h = seg & 1;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-      for (int w = 0; w < 8; ++w) {
-        const float *src = all + w * (NB * kRedFloats) + n * kRedFloats + (4 * q) * kRedStride + node + 32 * h;
-        v.x += src[0]; v.y += src[kRedStride]; v.z += src[2 * kRedStride]; v.w += src[3 * kRedStride];
-      }
-      const int row = n * 32 + node;
-      if (row < rows)
-        *reinterpret_cast<float4 *>(part + part_offset(s, row, band * 32 + seg * 4, n_bands, rows_pad)) = v;
-    }
+    if (NR == 0 && (int)threadIdx.x < NB * 256) sum_and_store(threadIdx.x, unit);
   };
   int unit = 0;
   for (; unit + 1 < n_units; ++unit) do_band(unit, std::true_type{});
@@ -165,11 +184,12 @@ template <int NB, int LW, int STAGE>
 static void launch_gemm_t(const PackedMatrix &W, const uint16_t *Xp, int rows, float *part,
                           const GemmPlan &plan, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const size_t lds = gemm_lds_bytes<NB>();
+  constexpr int block = 512 + 64 * gemm_reducers<NB, LW>();
   if (ev0 != nullptr)  // the events take the start and stop time of this dispatch itself
-    hipExtLaunchKernelGGL((gemm_skinny_kernel<NB, LW, STAGE>), dim3(plan.grid), dim3(512), (uint32_t)lds, st, ev0, ev1, 0u,
+    hipExtLaunchKernelGGL((gemm_skinny_kernel<NB, LW, STAGE>), dim3(plan.grid), dim3(block), (uint32_t)lds, st, ev0, ev1, 0u,
                           (const u32x4 *)W.data, (const u32x4 *)Xp, part, rows, W.n_bands, W.ksteps, plan.n_splits);
   else
-    gemm_skinny_kernel<NB, LW, STAGE><<<plan.grid, 512, lds, st>>>((const u32x4 *)W.data, (const u32x4 *)Xp, part, rows, W.n_bands, W.ksteps, plan.n_splits);
+    gemm_skinny_kernel<NB, LW, STAGE><<<plan.grid, block, lds, st>>>((const u32x4 *)W.data, (const u32x4 *)Xp, part, rows, W.n_bands, W.ksteps, plan.n_splits);
 }
 
 template <int STAGE>
