@@ -31,7 +31,10 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
 }
 
-// grid (n_chunks, Hkv * n_rgb, batch), block 256: the four wavefronts of a workgroup take the
+// grid (8 * n_rgb * ceil(n_chunks * Hkv / 8), 1, batch), block 256.  Workgroups go to the 8 XCDs
+// round-robin by their linear index, so the n_rgb workgroups that stream the SAME keys for
+// different query row groups are placed 8 apart: they run on one XCD and share its L2.
+// Block 256: the four wavefronts of a workgroup take the
 // 32-key tiles of the chunk round-robin, each with its own online softmax, and merge their
 // (max, sum, output) through LDS into ONE partial result per chunk.  RGW = query row groups (of
 // 32) per workgroup.
@@ -42,7 +45,8 @@ __global__ __launch_bounds__(256) void tree_attention_kernel(StepMeta m, KvGeom 
                                                             const uint16_t *__restrict__ qb_lo,
                                                             const uint16_t *__restrict__ kc,
                                                             const uint16_t *__restrict__ vc,
-                                                            int chunk_keys, float *__restrict__ o_part,
+                                                            int chunk_keys, int n_chunks,
+                                                            float *__restrict__ o_part,
                                                             float *__restrict__ ml_part) {
   constexpr int KK = HD / 16;  // MFMA k-steps across the head dimension
   constexpr int CB = HD / 32;  // 32-wide output column blocks
@@ -52,7 +56,9 @@ __global__ __launch_bounds__(256) void tree_attention_kernel(StepMeta m, KvGeom 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   uint32_t *vp = lds_attn + wave * (2 * 16 * HD);
   const int lane = threadIdx.x & 63, h = lane >> 5, ql = lane & 31;
-  const int chunk = blockIdx.x, kvh = blockIdx.y / n_rgb, rgb = blockIdx.y % n_rgb, seq = blockIdx.z;
+  const int rgb = (blockIdx.x >> 3) % n_rgb, base = ((blockIdx.x >> 3) / n_rgb) * 8 + (blockIdx.x & 7);
+  if (base >= n_chunks * Hkv) return;
+  const int chunk = base % n_chunks, kvh = base / n_chunks, seq = blockIdx.z;
   const int G = H / Hkv;
   const int L = m.seq_kv_len(seq), n = m.seq_n_nodes(seq), r0 = m.seq_row_start(seq), rows = m.rows;
   const int T = L + n, QR = G * n;
@@ -334,12 +340,12 @@ static void launch_attn_hd(const StepMeta &m, const ModelDims &md, const KvGeom 
   };
   // two row groups per workgroup only where their accumulators fit the register file (head_dim 64)
   if (row_groups <= 1 || HD > 64) {
-    dim3 grid(n_chunks, md.n_kv_heads * row_groups, m.batch);
-    tree_attention_kernel<HD, 1><<<grid, 256, lds_bytes(1), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, row_groups, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, o_part, ml_part);
+    dim3 grid((n_chunks * md.n_kv_heads + 7) / 8 * 8 * row_groups, 1, m.batch);
+    tree_attention_kernel<HD, 1><<<grid, 256, lds_bytes(1), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, row_groups, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, n_chunks, o_part, ml_part);
   } else {
     const int n_rgb = (row_groups + 1) / 2;
-    dim3 grid(n_chunks, md.n_kv_heads * n_rgb, m.batch);
-    tree_attention_kernel<HD, 2><<<grid, 256, lds_bytes(2), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, n_rgb, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, o_part, ml_part);
+    dim3 grid((n_chunks * md.n_kv_heads + 7) / 8 * 8 * n_rgb, 1, m.batch);
+    tree_attention_kernel<HD, 2><<<grid, 256, lds_bytes(2), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, n_rgb, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, n_chunks, o_part, ml_part);
   }
   dim3 mgrid(md.n_heads, m.rows);
   tree_attention_merge_kernel<<<mgrid, HD, 0, st>>>(m, md.n_heads, HD, chunk_keys, o_part, ml_part, out, out_lo, m.rows <= 32 ? 1 : 2);
