@@ -12,9 +12,9 @@ Two independent forms:
 Only tests, the smoke check and the benchmark's cpu_baseline leg import this
 package.  It shares no code with the HIP library.
 """
-from .tree import (OracleModel, build_oracle, tree_meta, accept, rmsnorm, rope, softmax,
+from .tree import (OracleModel, build_oracle, tree_meta, accept, top2, rmsnorm, rope, softmax,
                    silu, num_threads)
 from . import form_s
 
-__all__ = ["OracleModel", "build_oracle", "tree_meta", "accept", "rmsnorm", "rope",
+__all__ = ["OracleModel", "build_oracle", "tree_meta", "accept", "top2", "rmsnorm", "rope",
            "softmax", "silu", "num_threads", "form_s"]

@@ -360,6 +360,40 @@ int oracle_accept(const int32_t *tokens, const int32_t *parents, const int32_t *
   return 0;
 }
 
+/*
+ * Draft-side read-out of logit rows.  The draft model's confidence in a predicted token is its
+ * normalised logit, i.e. its softmax probability, which is compared with a threshold to decide
+ * where a draft is cut or marked as uncertain (Sec. IV-A; 0.4 in Sec. V-A); at uncertain positions
+ * the tokens of highest probability are kept and the one of second highest probability is the
+ * one expanded into a branch (Sec. IV-C, Sec. V-C).
+ *
+ * For each of the n rows x[0..V):
+ *   top[2r]   = the id of the largest logit (lowest id among equals)
+ *   top[2r+1] = the id of the largest logit among the other ids (lowest id among equals),
+ *               -1 when V == 1
+ *   p1[r]     = exp(x[top0]) / sum_j exp(x[j]), evaluated as 1 / sum_j exp(x[j] - x[top0])
+ */
+int oracle_top2(const double *logits, int n, int V, int32_t *top, double *p1) {
+  if (n < 0 || V < 1) return -1;
+  for (int r = 0; r < n; ++r) {
+    const double *x = logits + (size_t)r * V;
+    int a = 0;
+    for (int j = 1; j < V; ++j)
+      if (x[j] > x[a]) a = j;
+    int b = -1;
+    for (int j = 0; j < V; ++j) {
+      if (j == a) continue;
+      if (b < 0 || x[j] > x[b]) b = j;
+    }
+    double sum = 0.0;
+    for (int j = 0; j < V; ++j) sum += exp(x[j] - x[a]);
+    top[2 * r] = a;
+    top[2 * r + 1] = b;
+    p1[r] = 1.0 / sum;
+  }
+  return 0;
+}
+
 int oracle_num_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();

@@ -53,6 +53,7 @@ def _load():
         lib.oracle_tree_meta.restype = C.c_int
         lib.oracle_tree_forward.restype = C.c_int
         lib.oracle_accept.restype = C.c_int
+        lib.oracle_top2.restype = C.c_int
         lib.oracle_silu.restype = C.c_double
         lib.oracle_silu.argtypes = [C.c_double]
         lib.oracle_num_threads.restype = C.c_int
@@ -104,6 +105,20 @@ def accept(tokens, parents, amax):
     if rc != 0:
         raise ValueError("invalid tree")
     return path[:alen.value].copy(), int(alen.value), int(nxt.value)
+
+
+def top2(logits):
+    """Draft-side read-out of logit rows [n][V]: (top int32 [n][2], p1 float64 [n]) = the ids of
+    the largest and second largest logit (lowest id on ties, -1 if there is no second) and the
+    softmax probability of the largest."""
+    x = np.ascontiguousarray(logits, np.float64)
+    n, V = x.shape
+    top = np.full((n, 2), -7, np.int32)
+    p1 = np.zeros(n, np.float64)
+    rc = _load().oracle_top2(_p(x), C.c_int(n), C.c_int(V), _p(top), _p(p1))
+    if rc != 0:
+        raise ValueError("invalid shape")
+    return top, p1
 
 
 def rmsnorm(x, g, eps):

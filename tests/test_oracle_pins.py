@@ -475,3 +475,62 @@ def test_oracle_regression_against_stored_results():
         assert got[k] == want[k], k
     for k in ("logits_node0_first8", "logits_node7_first8"):
         assert np.allclose(got[k], want[k], rtol=1e-9, atol=1e-12)
+
+
+# --------------------------------------------------------------------------- draft-side read-out
+def test_top2_closed_forms_and_ties():
+    """Values that follow from the definition alone (Sec. IV-A normalised logit; Sec. IV-C tokens
+    of highest probability): equal logits, a two-token row with a known ratio, shift
+    invariance, no overflow, a single-token vocabulary, ties resolved towards the lower id."""
+    top, p = oracle.top2(np.zeros((1, 7)))
+    assert top.tolist() == [[0, 1]] and abs(p[0] - 1 / 7) < 1e-15
+    top, p = oracle.top2(np.array([[0.0, np.log(3.0)]]))
+    assert top.tolist() == [[1, 0]] and abs(p[0] - 0.75) < 1e-15
+    x = np.array([[0.3, -1.2, 2.5, 2.4, 0.0]])
+    t0, p0 = oracle.top2(x)
+    t1, p1 = oracle.top2(x + 1000.0)                      # would overflow without the max shift
+    assert t0.tolist() == t1.tolist() == [[2, 3]] and abs(p0[0] - p1[0]) < 1e-12
+    assert abs(p0[0] - np.exp(2.5) / np.exp(x).sum()) < 1e-15
+    top, p = oracle.top2(np.array([[4.2]]))
+    assert top.tolist() == [[0, -1]] and p[0] == 1.0
+    top, p = oracle.top2(np.array([[5.0, 1.0, 5.0, 5.0], [1.0, 7.0, 7.0, 0.0], [2.0, 9.0, 2.0, 1.0]]))
+    assert top.tolist() == [[0, 2], [1, 2], [1, 0]]
+    assert abs(p[0] - 1 / (3 + np.exp(-4.0))) < 1e-15
+    # a dominant logit: probability -> 1, the runner-up is still reported
+    top, p = oracle.top2(np.array([[0.0, 50.0, 1.0]]))
+    assert top.tolist() == [[1, 2]] and 1 - p[0] < 1e-20 + 2e-21 + np.exp(-49.0) * 1.1
+
+
+def test_top2_against_sort_and_library_softmax():
+    """Random rows (with planted duplicates of the two largest values): the two ids equal the head
+    of a (value descending, id ascending) sort, p1 equals scipy's softmax at the first id."""
+    from scipy.special import softmax as sp_softmax
+    rng = np.random.default_rng(404)
+    for V in (2, 3, 17, 1000):
+        x = rng.standard_normal((40, V)) * 3.0
+        for r in range(0, 40, 4):                          # exact ties among the leaders
+            j, k = rng.integers(0, V, 2)
+            x[r, j] = x[r].max()
+            x[r, k] = np.sort(x[r])[-2] if r % 8 else x[r].max()
+        top, p = oracle.top2(x)
+        ids = np.arange(V)
+        for r in range(40):
+            order = np.lexsort((ids, -x[r]))
+            assert top[r].tolist() == order[:2].tolist()
+            assert abs(p[r] - sp_softmax(x[r])[order[0]]) < 1e-14
+            assert x[r, top[r, 0]] >= x[r, top[r, 1]]
+
+
+def test_top2_first_id_is_the_forward_pass_argmax():
+    """On the logits of a tree forward, the first id of the read-out is the argmax the verify
+    path uses (same tie rule), for every node."""
+    cfg = dict(TINY)
+    w = _boost(wl.make_weights(cfg, 35, "f32"), 4.0)
+    om = oracle.OracleModel(cfg, w)
+    kc, vc = om.empty_cache(16)
+    parents = wl.tree_cfg1()
+    tokens = np.random.default_rng(36).integers(0, cfg["vocab"], 8).astype(np.int32)
+    r = om.tree_forward(kc, vc, 0, tokens, parents)
+    top, p = oracle.top2(r["logits"])
+    assert top[:, 0].tolist() == r["amax"].tolist()
+    assert np.all((p > 0) & (p <= 1))
