@@ -7,6 +7,10 @@ KV cache, LM head + per-node argmax, greedy acceptance, in-place KV compaction, 
 device-to-host copy of the results.  Weights, KV cache and tree live in HBM before the timed
 region starts; kv_len is reset on the host between steps.
 
+With `--workload draft_1b_recycle` the step is the draft-side tree forward instead
+(specasr_tree_forward_top2 on the recycling tree: the two most probable ids per node and the
+probability of the first); its line carries the metric draft_tree_forward_steps_per_s.
+
 Prints ONE JSON line.  Usage: python bench.py [--gpus 1] [--steps K] [--warmup W]
 """
 import argparse
@@ -33,17 +37,21 @@ def algorithmic_bytes(cfg, kv_len, n_nodes):
     return weights + kv_prefix + kv_tree, weights, kv_prefix
 
 
-def cpu_baseline(cfg, w_host, kc, vc, kv_len, tokens, parents, reps):
-    """The oracle, as it stands, on the host cores: the SAME verify step (tree forward over every
-    layer + LM head + argmax, then acceptance), repeated `reps` times; mean time per step."""
+def cpu_baseline(cfg, w_host, kc, vc, kv_len, tokens, parents, reps, draft=False):
+    """The oracle, as it stands, on the host cores: the SAME step (tree forward over every layer +
+    LM head + argmax, then acceptance -- or, draft side, the top-2 read-out), repeated `reps`
+    times; mean time per step."""
     import numpy as np
     import oracle
     om = oracle.OracleModel(cfg, w_host)
     kcs, vcs = np.ascontiguousarray(kc[0]), np.ascontiguousarray(vc[0])
     t0 = time.perf_counter()
     for _ in range(reps):
-        r = om.tree_forward(kcs, vcs, kv_len, tokens, parents, want_logits=False)
-        oracle.accept(tokens, parents, r["amax"])
+        r = om.tree_forward(kcs, vcs, kv_len, tokens, parents, want_logits=draft)
+        if draft:
+            oracle.top2(r["logits"])
+        else:
+            oracle.accept(tokens, parents, r["amax"])
     spent = time.perf_counter() - t0
     return spent / reps, spent, oracle.num_threads()
 
@@ -101,9 +109,15 @@ def main():
 
     stage_id = ["qkv", "o", "gate_up", "down", "lm_head"].index(args.stage)
 
+    draft = isinstance(spec["tree"], dict) and "two_branch" in spec["tree"]
+
     def step_with(tok):
         ver.kv_len[0] = kv_len
-        out = ver.verify_tree([tok], [parents])
+        if draft:                                  # no acceptance on the draft side
+            out = ver.tree_forward_top2([tok], [parents])
+            out["accept_len"] = [0]
+        else:
+            out = ver.verify_tree([tok], [parents])
         assert out["status"] == 0, out["status"]
         return out
 
@@ -143,17 +157,18 @@ def main():
         if not kids:
             break
         trunk.append(kids[0])
-    for _ in range(len(trunk)):
-        o2 = step_with(planted)
-        for a, b in zip(trunk[:-1], trunk[1:]):
-            planted[b] = o2["argmax"][0, a]
-    acc2 = 0
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for _ in range(args.steps):
-        acc2 += int(step_with(planted)["accept_len"][0])
-    torch.cuda.synchronize()
-    dt2 = time.perf_counter() - t1
+    acc2, dt2 = 0, float("nan")
+    if not draft:
+        for _ in range(len(trunk)):
+            o2 = step_with(planted)
+            for a, b in zip(trunk[:-1], trunk[1:]):
+                planted[b] = o2["argmax"][0, a]
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            acc2 += int(step_with(planted)["accept_len"][0])
+        torch.cuda.synchronize()
+        dt2 = time.perf_counter() - t1
 
     ms_per_step = dt / args.steps * 1e3
     steps_per_s = args.steps / dt
@@ -168,7 +183,8 @@ def main():
         traffic = json.load(open(tfile)).get("hbm_bytes_per_launch")
 
     result = {
-        "metric": "tree_verify_steps_per_s", "value": round(steps_per_s, 3), "unit": "steps/s",
+        "metric": "draft_tree_forward_steps_per_s" if draft else "tree_verify_steps_per_s",
+        "value": round(steps_per_s, 3), "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
@@ -176,9 +192,9 @@ def main():
                    "kv_prefix": kv_len, "batch": 1},
         "verified_tokens_per_s": round(accepted / dt, 2),
         "accept_len_mean": round(accepted / args.steps, 3),
-        "planted_trunk": {"accept_len_mean": round(acc2 / args.steps, 3),
-                          "verified_tokens_per_s": round(acc2 / dt2, 1),
-                          "ms_per_step": round(dt2 / args.steps * 1e3, 4)},
+        "planted_trunk": None if draft else {"accept_len_mean": round(acc2 / args.steps, 3),
+                                             "verified_tokens_per_s": round(acc2 / dt2, 1),
+                                             "ms_per_step": round(dt2 / args.steps * 1e3, 4)},
         "algorithmic_bytes_per_step": total_bytes,
         "step_hbm_gbs": round(step_gbs, 1), "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4),
         "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel (%s projection)" % args.stage,
@@ -192,12 +208,13 @@ def main():
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample")
         kh, vh = ver.get_cache()
-        est, spent, cores = cpu_baseline(cfg, w_host, kh, vh, kv_len, tokens, parents, args.cpu_reps)
+        est, spent, cores = cpu_baseline(cfg, w_host, kh, vh, kv_len, tokens, parents, args.cpu_reps, draft)
         result["cpu_baseline"] = {
             "value": round(1.0 / est, 5), "unit": "steps/s", "cores": cores, "kind": "oracle",
-            "sample": "fp64 oracle, the whole verify step of this workload (all %d layers, LM head, "
-                      "argmax, acceptance), %d repetitions = %.1f s of CPU work"
-                      % (cfg["n_layers"], args.cpu_reps, spent),
+            "sample": "fp64 oracle, the whole step of this workload (all %d layers, LM head, %s), "
+                      "%d repetitions = %.1f s of CPU work"
+                      % (cfg["n_layers"], "top-2 read-out" if draft else "argmax, acceptance",
+                         args.cpu_reps, spent),
             "ms_per_step": round(est * 1e3, 1)}
     print(json.dumps(result), flush=True)
     ver.close()

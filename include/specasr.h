@@ -157,6 +157,23 @@ specasr_status specasr_tree_forward(specasr_ctx *ctx, specasr_kv *kv, const spec
                                     int32_t *argmax_dev, float *logits_dev, void *workspace,
                                     size_t workspace_bytes, void *stream);
 
+/* Draft-side tree forward (Sec. IV-B: the draft model runs on a masked token tree -- the old draft
+ * as one branch, the part being regenerated as the other -- so that regeneration and reuse
+ * proceed in one pass; Sec. IV-A: the normalised logit of each predicted token is compared with
+ * a threshold; Sec. IV-C: positions of low confidence keep the tokens of highest probability and
+ * the second one is expanded).  Same kernels and the same semantics as specasr_tree_forward (the
+ * K/V rows of the nodes are written to slots kv_len + node, kv_len itself is unchanged), with a
+ * different read-out per node:
+ *   top2_dev      DEVICE int32 [batch][max_nodes][2]: ids of the largest and the second largest
+ *                 logit (value descending, lower id first among equal values; the second is -1
+ *                 for a one-token vocabulary); entries of nodes >= n_nodes are not written
+ *   top1_prob_dev DEVICE float [batch][max_nodes]: softmax probability of the first id
+ *   logits_dev    optional DEVICE fp32 [batch][max_nodes][vocab], or NULL
+ * Asynchronous on `stream`; errors as specasr_tree_forward. */
+specasr_status specasr_tree_forward_top2(specasr_ctx *ctx, specasr_kv *kv, const specasr_tree *tree,
+                                         int32_t *top2_dev, float *top1_prob_dev, float *logits_dev,
+                                         void *workspace, size_t workspace_bytes, void *stream);
+
 /* Stage: greedy acceptance (Sec. II-B: accept matching draft tokens, stop at the
  * first failure) from a DEVICE argmax array.  A draft node matches when its token
  * equals the argmax at its parent; the result is the deepest node whose whole

@@ -29,7 +29,8 @@ SPECASR_FLAG_NO_REPACK = 2
 SPECASR_MAX_NODES = 64
 
 EXPORTS = ("specasr_create", "specasr_destroy", "specasr_workspace_bytes", "specasr_verify_tree",
-           "specasr_tree_forward", "specasr_accept", "specasr_accept_from_logits",
+           "specasr_tree_forward", "specasr_tree_forward_top2", "specasr_accept",
+           "specasr_accept_from_logits",
            "specasr_commit", "specasr_strerror", "specasr_last_hip_error", "specasr_abi_version",
            "specasr_uses_mfma", "specasr_profile_stage", "specasr_stage_time")
 SPECASR_STAGE_QKV, SPECASR_STAGE_O, SPECASR_STAGE_GATE_UP, SPECASR_STAGE_DOWN, SPECASR_STAGE_LM_HEAD = range(5)
@@ -97,6 +98,9 @@ def load_library(path=None):
     lib.specasr_tree_forward.restype = C.c_int
     lib.specasr_tree_forward.argtypes = [vp, C.POINTER(specasr_kv), C.POINTER(specasr_tree), vp, vp,
                                          vp, C.c_size_t, vp]
+    lib.specasr_tree_forward_top2.restype = C.c_int
+    lib.specasr_tree_forward_top2.argtypes = [vp, C.POINTER(specasr_kv), C.POINTER(specasr_tree), vp,
+                                              vp, vp, vp, C.c_size_t, vp]
     lib.specasr_accept.restype = C.c_int
     lib.specasr_accept.argtypes = [vp, C.POINTER(specasr_tree), C.c_int32, vp, vp, vp, vp, vp,
                                    C.c_size_t, vp]
@@ -234,6 +238,13 @@ def specasr_tree_forward(ctx, kv, tree, argmax_dev, logits_dev, workspace, works
     return load_library().specasr_tree_forward(ctx, C.byref(kv), C.byref(tree), _ptr(argmax_dev),
                                                _ptr(logits_dev), _ptr(workspace), workspace_bytes,
                                                _ptr(stream))
+
+
+def specasr_tree_forward_top2(ctx, kv, tree, top2_dev, top1_prob_dev, logits_dev, workspace,
+                              workspace_bytes, stream=None):
+    return load_library().specasr_tree_forward_top2(ctx, C.byref(kv), C.byref(tree), _ptr(top2_dev),
+                                                    _ptr(top1_prob_dev), _ptr(logits_dev),
+                                                    _ptr(workspace), workspace_bytes, _ptr(stream))
 
 
 def specasr_accept(ctx, tree, batch, argmax_dev, path_dev, accept_len_dev, next_token_dev,

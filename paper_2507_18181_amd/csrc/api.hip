@@ -30,7 +30,7 @@ struct Staging {
 
 // offsets (in bytes) of the regions of a workspace sized for `rows_max` rows / `batch` sequences
 struct WsLayout {
-  size_t meta, outs, rope, x, h, q, k, v, att, gu, t, logits, total;
+  size_t meta, outs, rope, x, h, q, k, v, att, gu, t, logits, top2_v, top2_i, total;
   size_t hb, attb, tb, part, ssq, blk_val, blk_idx;  // bf16 activations and split-k partial sums (MFMA path)
   size_t qb, attn_o, attn_ml;                   // MFMA attention: bf16 queries, per-chunk partial outputs
   size_t meta_words;
@@ -136,6 +136,8 @@ WsLayout ws_layout(const specasr_config &c, int batch) {
   L.gu = take(R * 2 * c.d_ffn * 4);
   L.t = take(R * c.d_ffn * 4);
   L.logits = take(R * c.vocab * 4);
+  L.top2_v = take(R * (size_t)top2_blocks(c.vocab) * 3 * 4);
+  L.top2_i = take(R * (size_t)top2_blocks(c.vocab) * 2 * 4);
   L.total = off;
   return L;
 }
@@ -318,10 +320,22 @@ specasr_status check_ws(const specasr_ctx *ctx, const void *ws, size_t bytes, in
   return SPECASR_OK;
 }
 
+// What a forward leaves behind (device pointers in [batch][max_nodes] layout, already offset to
+// the first sequence of the call or group).  Either argmax, or the draft-side read-out top2 +
+// prob (then argmax is optional); logits always optional.
+struct ReadOut {
+  int32_t *argmax = nullptr;
+  float *logits = nullptr;
+  int32_t *top2 = nullptr;
+  float *prob = nullptr;
+};
+
 // Steps 1-8 with the dtype-generic kernels.
 void forward_generic(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_kv *kv,
-                     const specasr_tree *tree, char *ws, const WsLayout &L, int32_t *argmax_dev,
-                     float *logits_dev, hipStream_t st) {
+                     const specasr_tree *tree, char *ws, const WsLayout &L, const ReadOut &ro,
+                     hipStream_t st) {
+  int32_t *argmax_dev = ro.argmax;
+  float *logits_dev = ro.logits;
   const ModelDims &md = ctx->md;
   const int dt = md.dtype, d = md.d_model, F = md.d_ffn, V = md.vocab;
   const int dq = md.n_heads * md.head_dim, dkv = md.n_kv_heads * md.head_dim, R = m.rows;
@@ -349,7 +363,11 @@ void forward_generic(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, speca
   }
   launch_rmsnorm(dt, x, ctx->w.final_norm, R, d, md.rms_eps, h, st);
   launch_linear(dt, ctx->w.lm_head, V, d, h, d, lg, V, R, false, st);
-  launch_argmax(m, lg, false, ctx->cfg.max_nodes, V, argmax_dev, st);
+  if (ro.top2)
+    launch_top2(m, lg, false, 0, 0, RowNorm{nullptr, 0, 0, 0.f}, V, ctx->cfg.max_nodes, nullptr,
+                (float *)(ws + L.top2_v), (int *)(ws + L.top2_i), ro.top2, ro.prob, argmax_dev, st);
+  else
+    launch_argmax(m, lg, false, ctx->cfg.max_nodes, V, argmax_dev, st);
   if (logits_dev) launch_scatter_logits(m, lg, ctx->cfg.max_nodes, V, logits_dev, st);
 }
 
@@ -386,7 +404,9 @@ void gemm_stage(specasr_ctx *ctx, int stage, bool profiled_layer, const PackedMa
 // SwiGLU output) are rounded to bf16.
 void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_kv *kv,
                   const specasr_tree *tree, char *ws, const WsLayout &L, const HostStep &hs,
-                  int32_t *argmax_dev, float *logits_dev, hipStream_t st) {
+                  const ReadOut &ro, hipStream_t st) {
+  int32_t *argmax_dev = ro.argmax;
+  float *logits_dev = ro.logits;
   const ModelDims &md = ctx->md;
   const int d = md.d_model, F = md.d_ffn, V = md.vocab, R = m.rows;
   const int dq = md.n_heads * md.head_dim;
@@ -457,19 +477,23 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
   }
   launch_residual_gain(x, part, pending, R, pending_ld, ctx->w.final_norm, d, hb, hb_lo, ssq, st);
   gemm_stage(ctx, SPECASR_STAGE_LM_HEAD, true, ctx->lm_head, hb, R, part, pl_lm, st);
-  launch_logits_argmax(m, part, pl_lm.n_splits, ctx->lm_head.ldo, nrm, V, ctx->cfg.max_nodes, logits_dev,
-                       (float *)(ws + L.blk_val), (int *)(ws + L.blk_idx), argmax_dev, st);
+  if (ro.top2)
+    launch_top2(m, part, true, pl_lm.n_splits, ctx->lm_head.ldo, nrm, V, ctx->cfg.max_nodes, logits_dev,
+                (float *)(ws + L.top2_v), (int *)(ws + L.top2_i), ro.top2, ro.prob, argmax_dev, st);
+  else
+    launch_logits_argmax(m, part, pl_lm.n_splits, ctx->lm_head.ldo, nrm, V, ctx->cfg.max_nodes, logits_dev,
+                         (float *)(ws + L.blk_val), (int *)(ws + L.blk_idx), argmax_dev, st);
 }
 
 specasr_status forward_common(specasr_ctx *ctx, specasr_kv *kv, const specasr_tree *tree,
-                              int32_t *argmax_dev, float *logits_dev, char *ws,
-                              const WsLayout &L, const HostStep &hs, hipStream_t st) {
+                              const ReadOut &ro, char *ws, const WsLayout &L, const HostStep &hs,
+                              hipStream_t st) {
   KvGeom g{kv->capacity, ctx->md.n_layers, ctx->md.n_kv_heads, ctx->md.head_dim};
   StepMeta m = device_meta(ctx, ws, L, hs.batch, hs);
   if (ctx->fast && m.rows <= 64)
-    forward_fast(ctx, m, g, kv, tree, ws, L, hs, argmax_dev, logits_dev, st);
+    forward_fast(ctx, m, g, kv, tree, ws, L, hs, ro, st);
   else
-    forward_generic(ctx, m, g, kv, tree, ws, L, argmax_dev, logits_dev, st);
+    forward_generic(ctx, m, g, kv, tree, ws, L, ro, st);
   HIP_TRY(ctx, hipGetLastError());
   return SPECASR_OK;
 }
@@ -730,8 +754,39 @@ specasr_status specasr_tree_forward(specasr_ctx *ctx, specasr_kv *kv, const spec
     build_step(ctx, &grp.tree, grp.kv.batch, grp.kv.kv_len, &hs);
     s = upload_meta(ctx, hs, ws, L, st);
     if (s != SPECASR_OK) return s;
-    s = forward_common(ctx, &grp.kv, &grp.tree, argmax_dev + grp.s0 * MN,
-                       logits_dev ? logits_dev + grp.s0 * MN * ctx->cfg.vocab : nullptr, ws, L, hs, st);
+    ReadOut ro;
+    ro.argmax = argmax_dev + grp.s0 * MN;
+    ro.logits = logits_dev ? logits_dev + grp.s0 * MN * ctx->cfg.vocab : nullptr;
+    s = forward_common(ctx, &grp.kv, &grp.tree, ro, ws, L, hs, st);
+    if (s != SPECASR_OK) return s;
+  }
+  return SPECASR_OK;
+}
+
+specasr_status specasr_tree_forward_top2(specasr_ctx *ctx, specasr_kv *kv, const specasr_tree *tree,
+                                         int32_t *top2_dev, float *top1_prob_dev, float *logits_dev,
+                                         void *workspace, size_t workspace_bytes, void *stream) {
+  if (!ctx || !top2_dev || !top1_prob_dev) return SPECASR_E_NULL;
+  specasr_status s = check_kv(kv);
+  if (s != SPECASR_OK) return s;
+  s = validate_tree(ctx, tree, kv->batch, kv->kv_len, kv->capacity, true);
+  if (s != SPECASR_OK) return s;
+  s = check_ws(ctx, workspace, workspace_bytes, kv->batch);
+  if (s != SPECASR_OK) return s;
+  hipStream_t st = (hipStream_t)stream;
+  char *ws = (char *)workspace;
+  const WsLayout L = ws_layout(ctx, kv->batch);
+  const size_t MN = (size_t)ctx->cfg.max_nodes;
+  for (SeqGroup &grp : split_call(ctx, kv, tree)) {
+    HostStep hs;
+    build_step(ctx, &grp.tree, grp.kv.batch, grp.kv.kv_len, &hs);
+    s = upload_meta(ctx, hs, ws, L, st);
+    if (s != SPECASR_OK) return s;
+    ReadOut ro;
+    ro.top2 = top2_dev + grp.s0 * MN * 2;
+    ro.prob = top1_prob_dev + grp.s0 * MN;
+    ro.logits = logits_dev ? logits_dev + grp.s0 * MN * ctx->cfg.vocab : nullptr;
+    s = forward_common(ctx, &grp.kv, &grp.tree, ro, ws, L, hs, st);
     if (s != SPECASR_OK) return s;
   }
   return SPECASR_OK;
@@ -858,8 +913,10 @@ specasr_status specasr_verify_tree(specasr_ctx *ctx, specasr_kv *kv, const speca
     build_step(ctx, &grp.tree, grp.kv.batch, grp.kv.kv_len, &hs);
     s = upload_meta(ctx, hs, ws, L, st);
     if (s != SPECASR_OK) return s;
-    s = forward_common(ctx, &grp.kv, &grp.tree, argmax_dev + grp.s0 * MN,
-                       out->logits ? out->logits + grp.s0 * MN * c.vocab : nullptr, ws, L, hs, st);
+    ReadOut ro;
+    ro.argmax = argmax_dev + grp.s0 * MN;
+    ro.logits = out->logits ? out->logits + grp.s0 * MN * c.vocab : nullptr;
+    s = forward_common(ctx, &grp.kv, &grp.tree, ro, ws, L, hs, st);
     if (s != SPECASR_OK) return s;
     StepMeta m = device_meta(ctx, ws, L, grp.kv.batch, hs);
     KvGeom g{kv->capacity, c.n_layers, c.n_kv_heads, c.head_dim};

@@ -122,4 +122,20 @@ __device__ __forceinline__ float block_max(float v, float *red) {
   return t;
 }
 
+// Per-row RMSNorm statistics left by launch_residual_gain for the consumer of the next GEMM.
+struct RowNorm {
+  const float *ssq;  // [rows][n_slab] sums of squares of the residual row, one per column slab
+  int n_slab;
+  int d;      // row length
+  float eps;  // added to the mean square inside the root
+};
+// 1 / rms of residual row r from the slab sums of squares (eps inside the root, Sec. II-A's decoder
+// block).  Every lane of the calling wavefront must be active; all lanes get the same value.
+__device__ __forceinline__ float row_rms_scale(const RowNorm &nrm, int r) {
+  float s = 0.f;
+  for (int i = threadIdx.x & 63; i < nrm.n_slab; i += 64) s += nrm.ssq[(int64_t)r * nrm.n_slab + i];
+  s = wave_sum(s);
+  return 1.0f / sqrtf(s / (float)nrm.d + nrm.eps);
+}
+
 }  // namespace specasr

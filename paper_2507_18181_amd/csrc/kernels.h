@@ -41,6 +41,16 @@ void launch_argmax(const StepMeta &m, const float *logits, bool padded_in, int m
 void launch_scatter_logits(const StepMeta &m, const float *compact, int max_nodes, int V,
                            float *padded, hipStream_t st);
 
+// Draft-side read-out (Sec. IV-A, Sec. IV-C): top2[seq][node] = ids of the largest and second
+// largest logit (value descending, id ascending; second = -1 if V == 1), prob[seq][node] = softmax
+// probability of the first, argmax (optional) = the first id.  The logits are compact rows
+// [rows][V], or (from_partials) split-k partial sums, times 1/rms of the row if nrm.ssq is set,
+// that are also stored into logits_out ([batch][max_nodes][V], optional).  rec_v / rec_i: rows * top2_blocks(V) * 3 floats / 2 ints.
+int top2_blocks(int V);
+void launch_top2(const StepMeta &m, const float *src, bool from_partials, int n_splits, int ldp,
+                 const RowNorm &nrm, int V, int max_nodes, float *logits_out, float *rec_v, int *rec_i, int32_t *top2,
+                 float *prob, int32_t *argmax, hipStream_t st);
+
 // ---- integer stages --------------------------------------------------------
 // greedy acceptance, one wavefront per sequence; argmax in [batch][max_nodes] layout
 void launch_accept(const StepMeta &m, int max_nodes, const int32_t *argmax, int32_t *path,

@@ -308,6 +308,148 @@ void launch_scatter_logits(const StepMeta &m, const float *compact, int max_node
   scatter_logits_kernel<<<grid, 256, 0, st>>>(m, compact, max_nodes, V, padded);
 }
 
+// --------------------------------------------------------------------------- draft-side read-out
+// Per row: the ids of the largest and the second largest logit and the softmax probability of
+// the largest -- the draft model's normalised logit that is compared with a threshold, and the
+// candidate of second highest probability that a sparse tree expands (Sec. IV-A, Sec. IV-C).
+// Order: value descending, id ascending among equal values.
+struct Top2 {
+  float v1, v2;
+  int i1, i2;
+};
+__device__ __forceinline__ bool top2_before(float a, int ia, float b, int ib) {
+  return a > b || (a == b && ia < ib);
+}
+__device__ __forceinline__ void top2_push(Top2 &t, float v, int i) {
+  if (top2_before(v, i, t.v1, t.i1)) {
+    t.v2 = t.v1; t.i2 = t.i1; t.v1 = v; t.i1 = i;
+  } else if (top2_before(v, i, t.v2, t.i2)) {
+    t.v2 = v; t.i2 = i;
+  }
+}
+__device__ __forceinline__ Top2 top2_merge(const Top2 &a, const Top2 &b) {
+  Top2 r = a;
+  top2_push(r, b.v1, b.i1);
+  top2_push(r, b.v2, b.i2);
+  return r;
+}
+__device__ __forceinline__ Top2 top2_wave(Top2 t) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    Top2 u;
+    u.v1 = __shfl_xor(t.v1, o, 64); u.v2 = __shfl_xor(t.v2, o, 64);
+    u.i1 = __shfl_xor(t.i1, o, 64); u.i2 = __shfl_xor(t.i2, o, 64);
+    t = top2_merge(t, u);
+  }
+  return t;
+}
+constexpr int kNoId = 0x7fffffff;
+
+// Stage 1, grid (blocks of 1024 ids, rows), block 256, 4 consecutive ids per thread.  SRC = 0: the
+// logits are compact rows [rows][V]; SRC = 1: they are split-k partial sums (part_offset) that
+// are summed here, multiplied by 1/rms of the row when nrm.ssq is set (second half of the final
+// RMSNorm), and optionally stored into the caller's padded [batch][max_nodes][V] array.
+// Record per (row, block): (v1, v2, sum of exp(v - v1) over the block), (i1, i2).
+template <int SRC>
+__global__ __launch_bounds__(256) void top2_blocks_kernel(StepMeta m, const float *src, int n_splits,
+                                                          int ldp, RowNorm nrm, int V,
+                                                          int max_nodes, float *logits_out,
+                                                          float *rec_v, int *rec_i) {
+  __shared__ Top2 wt[4];
+  __shared__ float ws[4];
+  const int r = blockIdx.y, rows = m.rows;
+  const float rs = (SRC == 1 && nrm.ssq != nullptr) ? row_rms_scale(nrm, r) : 1.0f;
+  const int v0 = (blockIdx.x * 256 + threadIdx.x) * 4;
+  float vals[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+  if (v0 < V) {
+    if (SRC == 0) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (v0 + i < V) vals[i] = src[(int64_t)r * V + v0 + i];
+    } else {
+      float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int s = 0; s < n_splits; ++s) {
+        const float4 p = *reinterpret_cast<const float4 *>(src + part_offset(s, r, v0, ldp >> 5, part_rows_pad(rows)));
+        a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
+      }
+      const float t[4] = {a.x * rs, a.y * rs, a.z * rs, a.w * rs};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (v0 + i < V) vals[i] = t[i];
+    }
+    if (logits_out) {
+      float *dst = logits_out + ((int64_t)m.seq[r] * max_nodes + m.node[r]) * V + v0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (v0 + i < V) dst[i] = vals[i];
+    }
+  }
+  Top2 t{-INFINITY, -INFINITY, kNoId, kNoId};
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (v0 + i < V) top2_push(t, vals[i], v0 + i);
+  t = top2_wave(t);
+  if ((threadIdx.x & 63) == 0) wt[threadIdx.x >> 6] = t;
+  __syncthreads();
+  t = top2_merge(top2_merge(wt[0], wt[1]), top2_merge(wt[2], wt[3]));
+  float e = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (v0 + i < V) e += __expf(vals[i] - t.v1);
+  e = wave_sum(e);
+  if ((threadIdx.x & 63) == 0) ws[threadIdx.x >> 6] = e;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int64_t o = (int64_t)r * gridDim.x + blockIdx.x;
+    rec_v[o * 3] = t.v1;
+    rec_v[o * 3 + 1] = t.v2;
+    rec_v[o * 3 + 2] = (ws[0] + ws[1]) + (ws[2] + ws[3]);
+    rec_i[o * 2] = t.i1;
+    rec_i[o * 2 + 1] = t.i2;
+  }
+}
+
+// Stage 2, one wavefront per row: merge the block records.  p1 = 1 / sum_b s_b * exp(v1_b - v1).
+__global__ __launch_bounds__(64) void top2_merge_kernel(StepMeta m, const float *rec_v,
+                                                        const int *rec_i, int n_blk, int max_nodes,
+                                                        int32_t *top2, float *prob, int32_t *argmax) {
+  const int r = blockIdx.x;
+  Top2 t{-INFINITY, -INFINITY, kNoId, kNoId};
+  for (int b = threadIdx.x; b < n_blk; b += 64) {
+    const int64_t o = (int64_t)r * n_blk + b;
+    const Top2 u{rec_v[o * 3], rec_v[o * 3 + 1], rec_i[o * 2], rec_i[o * 2 + 1]};
+    t = top2_merge(t, u);
+  }
+  t = top2_wave(t);
+  float sum = 0.f;
+  for (int b = threadIdx.x; b < n_blk; b += 64) {
+    const int64_t o = (int64_t)r * n_blk + b;
+    sum += rec_v[o * 3 + 2] * __expf(rec_v[o * 3] - t.v1);
+  }
+  sum = wave_sum(sum);
+  if (threadIdx.x == 0) {
+    const int64_t orow = (int64_t)m.seq[r] * max_nodes + m.node[r];
+    top2[orow * 2] = t.i1 == kNoId ? 0 : t.i1;
+    top2[orow * 2 + 1] = t.i2 == kNoId ? -1 : t.i2;
+    prob[orow] = 1.0f / sum;
+    if (argmax) argmax[orow] = t.i1 == kNoId ? 0 : t.i1;
+  }
+}
+
+int top2_blocks(int V) { return ((V + 3) / 4 + 255) / 256; }
+
+void launch_top2(const StepMeta &m, const float *src, bool from_partials, int n_splits, int ldp,
+                 const RowNorm &nrm, int V, int max_nodes, float *logits_out, float *rec_v, int *rec_i, int32_t *top2,
+                 float *prob, int32_t *argmax, hipStream_t st) {
+  const int n_blk = top2_blocks(V);
+  dim3 grid(n_blk, m.rows);
+  if (from_partials)
+    top2_blocks_kernel<1><<<grid, 256, 0, st>>>(m, src, n_splits, ldp, nrm, V, max_nodes, logits_out, rec_v, rec_i);
+  else
+    top2_blocks_kernel<0><<<grid, 256, 0, st>>>(m, src, 0, 0, nrm, V, max_nodes, logits_out, rec_v, rec_i);
+  top2_merge_kernel<<<m.rows, 64, 0, st>>>(m, rec_v, rec_i, n_blk, max_nodes, top2, prob, argmax);
+}
+
 // --------------------------------------------------------------------------- acceptance
 // One wavefront per sequence, lane i = tree node i (trees have at most 64 nodes).
 // Sec. II-B: draft tokens are accepted while they match the target's output and

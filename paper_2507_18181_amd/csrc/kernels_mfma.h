@@ -24,13 +24,6 @@ hipError_t gemm_skinny_set_lds_limit();
 void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *Xp, int rows, float *part,
                         const GemmPlan &plan, int stage, hipStream_t st,
                         hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
-// Per-row RMSNorm statistics left by launch_residual_gain for the consumer of the next GEMM.
-struct RowNorm {
-  const float *ssq;  // [rows][n_slab] sums of squares of the residual row, one per column slab
-  int n_slab;
-  int d;      // row length
-  float eps;  // added to the mean square inside the root
-};
 int residual_slabs(int d);
 void launch_residual_gain(float *x, const float *part, int n_splits, int rows, int ldp,
                           const void *gain, int d, uint16_t *hb, uint16_t *hb_lo, float *ssq,

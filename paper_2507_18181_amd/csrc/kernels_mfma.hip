@@ -314,15 +314,6 @@ void launch_residual_gain(float *x, const float *part, int n_splits, int rows, i
   residual_gain_kernel<<<n_slab, ((rows + 7) / 8) * 64, 0, st>>>(x, part, n_splits, rows, ldp, (const uint16_t *)gain, d, hb, hb_lo, rows <= 32 ? 1 : 2, ssq, n_slab);
 }
 
-// 1 / rms of residual row r from the slab sums of squares (eps inside the root, Sec. II-A's decoder
-// block).  Every lane of the calling wavefront must be active; all lanes get the same value.
-__device__ __forceinline__ float row_rms_scale(const RowNorm &nrm, int r) {
-  float s = 0.f;
-  for (int i = threadIdx.x & 63; i < nrm.n_slab; i += 64) s += nrm.ssq[(int64_t)r * nrm.n_slab + i];
-  s = wave_sum(s);
-  return 1.0f / sqrtf(s / (float)nrm.d + nrm.eps);
-}
-
 // q, k, v = sum of partials; rotary embedding at the node's depth position (Sec. II-B: each
 // branch is verified as its own sequence, so position = kv_len + depth).  Outputs: q either as
 // fp32 [rows][H*hd] (generic attention) or as bf16 pre-multiplied by 1/sqrt(hd) (MFMA

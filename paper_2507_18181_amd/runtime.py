@@ -131,6 +131,23 @@ class Verifier:
         torch.cuda.synchronize()
         return dict(status=rc, argmax=argmax, logits=logits)
 
+    def tree_forward_top2(self, tokens, parents, want_logits=False, embeds=None, use_embed=None,
+                          stream=None):
+        """Draft-side forward: per node the two most probable token ids and the probability of
+        the first.  Returns dict(status, top2 [batch][max_nodes][2], prob, logits)."""
+        nb = self.batch
+        tree, keep = self._tree(tokens, parents, embeds, use_embed)
+        top2 = torch.full((nb, self.max_nodes, 2), -7, dtype=torch.int32, device=self.device)
+        prob = torch.full((nb, self.max_nodes), -1.0, dtype=torch.float32, device=self.device)
+        logits = None
+        if want_logits:
+            logits = torch.zeros((nb, self.max_nodes, self.cfg["vocab"]), dtype=torch.float32,
+                                 device=self.device)
+        rc = B.specasr_tree_forward_top2(self.ctx, self._kv, tree, top2, prob, logits, self.ws_ptr,
+                                         self.ws_bytes, stream)
+        torch.cuda.synchronize()
+        return dict(status=rc, top2=top2, prob=prob, logits=logits)
+
     def accept(self, tokens, parents, argmax_dev=None, logits_dev=None, stream=None):
         nb = len(tokens)
         tree, keep = self._tree(tokens, parents)

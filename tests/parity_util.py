@@ -40,6 +40,39 @@ def check_forward(ref, gpu_logits, gpu_argmax, tol):
     return dec
 
 
+def check_top2(logits_f32, top2, prob, n):
+    """The read-out of the draft-side forward against the oracle's read-out of THE SAME fp32
+    logits (the decision is taken on identical values on both sides): ids bit-exact, probability
+    of the first to 1e-5 relative (fp32 exp and summation over the vocabulary)."""
+    want_top, want_p = oracle.top2(np.asarray(logits_f32[:n], np.float64))
+    assert np.array_equal(np.asarray(top2[:n]), want_top)
+    rel = np.abs(np.asarray(prob[:n], np.float64) - want_p) / want_p
+    assert rel.max() <= 1e-5, rel.max()
+
+
+def check_top2_against_oracle_forward(ref_logits, top2, prob, logit_tol):
+    """Against the oracle's own forward.  Its logits differ from the GPU's by at most
+    eps = logit_tol * max|logit| per row, so every probability ratio moves by at most a factor
+    exp(2 eps); with R = (1 - p) / p this gives |p1 - p1_ref| = p_lo (1 - p_hi) (exp(2 eps) - 1)
+    <= 0.25 (exp(2 eps) - 1) (p_lo <= p_hi the two probabilities); 1e-6 is added for the fp32 sum.  The first id must agree where the oracle's gap between its
+    two largest logits exceeds GAP, the second where the gap below it does too."""
+    n = ref_logits.shape[0]
+    want_top, want_p = oracle.top2(ref_logits)
+    srt = np.sort(ref_logits, axis=1)
+    g12 = srt[:, -1] - srt[:, -2]
+    g23 = srt[:, -2] - srt[:, -3]
+    d1 = g12 > GAP
+    d2 = d1 & (g23 > GAP)
+    got = np.asarray(top2[:n])
+    assert np.array_equal(got[d1, 0], want_top[d1, 0])
+    assert np.array_equal(got[d2, 1], want_top[d2, 1])
+    eps = logit_tol * np.abs(ref_logits).max(axis=1)
+    bound = 0.25 * (np.exp(2 * eps) - 1) + 1e-6
+    dp = np.abs(np.asarray(prob[:n], np.float64) - want_p)
+    print("top-1 probability: max |dp| %.3e (bound %.3e), decisive %d/%d" % (dp.max(), bound.min(), d1.sum(), n))
+    assert np.all(dp <= bound)
+
+
 def check_tree_kv(kc_gpu, vc_gpu, L, ref, tol):
     """Rows L..L+n of one sequence's GPU cache ([layers][heads][cap][hd] storage) against the
     oracle's per-node K/V rows."""

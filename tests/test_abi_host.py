@@ -40,7 +40,7 @@ def ctx(lib):
 
 def test_exports_match_header(lib):
     hdr = open(os.path.join(ROOT, "include", "specasr.h")).read()
-    declared = set(re.findall(r"\b(specasr_[a-z_]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(specasr_[a-z0-9_]+)\s*\(", hdr))
     assert declared == set(B.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name

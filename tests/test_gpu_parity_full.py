@@ -9,7 +9,8 @@ import pytest
 
 import oracle
 import workload as wl
-from parity_util import TOL_BF16, check_forward, check_tree_kv, top2_gap, GAP, widen_cache
+from parity_util import (TOL_BF16, check_forward, check_tree_kv, top2_gap, GAP, widen_cache,
+                         check_top2, check_top2_against_oracle_forward)
 
 pytestmark = pytest.mark.gpu
 
@@ -135,6 +136,34 @@ def test_cfg2_planted_trunk_and_library_prefill(model_1b):
     out, ref = _round_checks(ver, om, tokens, parents, L)
     if np.all(top2_gap(ref["logits"])[:5] > GAP):
         assert out["accept_len"][0] == 5 and out["next_token"][0] == greedy[4]
+    ver.close()
+
+
+def test_draft_1b_two_branch_recycling_tree(model_1b):
+    """Draft side at its real size: the 1.1B-class model on the recycling tree (previous 24-token
+    draft as one branch, a 12-token regenerated part as the other, 37 nodes = two node groups),
+    prefix 330, read out as two most probable ids + probability of the first, in the launch
+    configuration `bench.py --workload draft_1b_recycle` times."""
+    spec = wl.WORKLOADS["draft_1b_recycle"]
+    cfg = model_1b.cfg
+    L = spec["n_audio"] + spec["n_text"]
+    parents, tokens = wl.make_tree("draft_1b_recycle")
+    n = len(parents)
+    assert n == 37
+    ver = model_1b.verifier(L + 64)
+    K, V = wl.seeded_cache(cfg, spec["seed"], L, L + 64, "bf16")
+    ver.set_cache(K, V, [L])
+    out = ver.tree_forward_top2([tokens], [parents], want_logits=True)
+    assert out["status"] == 0 and ver.kv_len[0] == L
+    lg = out["logits"][0].cpu().numpy()
+    top2 = out["top2"][0].cpu().numpy()
+    prob = out["prob"][0].cpu().numpy()
+    check_top2(lg, top2, prob, n)
+    ref = model_1b.om.tree_forward(np.ascontiguousarray(K[0]), np.ascontiguousarray(V[0]), L, tokens, parents)
+    check_forward(ref, lg, top2[:, 0], TOL_BF16)
+    check_top2_against_oracle_forward(ref["logits"], top2, prob, TOL_BF16)
+    k1, v1 = ver.get_cache()
+    check_tree_kv(k1[0], v1[0], L, ref, TOL_BF16)
     ver.close()
 
 

@@ -6,7 +6,8 @@ import oracle
 from oracle import form_s
 import workload as wl
 from parity_util import (TOL_F32, TOL_BF16, check_forward, check_tree_kv, oracle_prefilled,
-                         row_rel_err, widen_cache, walk_is_decisive)
+                         row_rel_err, widen_cache, walk_is_decisive, check_top2,
+                         check_top2_against_oracle_forward)
 
 pytestmark = pytest.mark.gpu
 
@@ -213,6 +214,59 @@ def test_batch_above_64_rows_runs_in_sequence_groups_on_the_mfma_path():
         got = widen_cache(k2[b, :, :, Ls[b]:Ls[b] + alen])
         assert np.abs(got - want).max() <= TOL_BF16 * np.abs(want).max()
         assert np.all(out["argmax"][b, n:] == -1)
+    ver.close()
+
+
+@pytest.mark.parametrize("dtype,flags,tol", [("f32", 0, TOL_F32), ("bf16", 1, TOL_BF16),
+                                             ("bf16", 0, TOL_BF16)])
+def test_draft_readout_two_branch_tree(dtype, flags, tol):
+    """Draft-side forward on the recycling tree (old draft and regenerated part as two branches
+    below the last verified token): per node the two most probable ids and the probability of
+    the first.  (a) read-out against the oracle's read-out of the SAME fp32 logits: ids exact,
+    probability 1e-5; (b) against the oracle's own forward within the bound the logit tolerance
+    implies; (c) logits and first id identical to specasr_tree_forward; (d) exact ties (two equal
+    LM-head rows) resolved towards the lower id in both positions; (e) the K/V rows of the nodes
+    are in the cache, kv_len is unchanged."""
+    cfg = wl.MODELS["tiny"]
+    w = wl.make_weights(cfg, 57, dtype)
+    lm = w["lm_head"]
+    for a, b in ((17, 901), (640, 5)):   # equal rows tie exactly; x4 (exact in both storage types)
+        row = wl.bf16_to_f32(lm[a]) * 4.0 if dtype == "bf16" else lm[a] * 4.0   # makes them frequent leaders
+        lm[a] = wl.bf16_bits(row) if dtype == "bf16" else row
+        lm[b] = lm[a]
+    tie_rows = 0
+    rng = np.random.default_rng(58)
+    L, cap = 41, 128
+    ver = _verifier(cfg, w, dtype, max_nodes=64, capacity=cap, flags=flags)
+    om = oracle.OracleModel(cfg, w)
+    K, V = wl.seeded_cache(cfg, 59, L, cap, dtype)
+    for parents in (wl.two_branch_tree(24, 9), wl.two_branch_tree(1, 1), np.array([-1], np.int32),
+                    wl.two_branch_tree(40, 23)):
+        n = len(parents)
+        tokens = wl.tree_tokens(rng, parents, cfg["vocab"])
+        ver.set_cache(K, V, [L])
+        out = ver.tree_forward_top2([tokens], [parents], want_logits=True)
+        assert out["status"] == 0 and ver.kv_len[0] == L
+        lg = out["logits"][0].cpu().numpy()
+        top2 = out["top2"][0].cpu().numpy()
+        prob = out["prob"][0].cpu().numpy()
+        check_top2(lg, top2, prob, n)
+        ref = om.tree_forward(np.ascontiguousarray(K[0]), np.ascontiguousarray(V[0]), L, tokens, parents)
+        check_top2_against_oracle_forward(ref["logits"], top2, prob, tol)
+        kc, vc = ver.get_cache()
+        check_tree_kv(kc[0], vc[0], L, ref, tol)
+        ver.set_cache(K, V, [L])
+        fwd = ver.tree_forward([tokens], [parents], want_logits=True)
+        assert torch.equal(fwd["logits"][0, :n], out["logits"][0, :n])
+        assert np.array_equal(fwd["argmax"][0, :n].cpu().numpy(), top2[:n, 0])
+        for a, b in ((17, 901), (640, 5)):
+            lo, hi = min(a, b), max(a, b)
+            assert np.all(lg[:n, a] == lg[:n, b])
+            assert not np.any(top2[:n, 0] == hi)             # the lower id always comes first
+            rows = np.nonzero(top2[:n, 0] == lo)[0]
+            assert np.all(top2[rows, 1] == hi)
+            tie_rows += len(rows)
+    assert tie_rows > 0
     ver.close()
 
 

@@ -39,6 +39,10 @@ WORKLOADS = {
     "cfg5_7b_n64": dict(model="7b", dtype="bf16", n_audio=3000, n_text=200, rounds=20,
                         tree=dict(trunk=24, n_branches=8, branch_depth=5, rule="lowest"),
                         seed=1005),
+    # draft side (Sec. IV-B): the 1.1B-class draft model on the recycling tree, previous 24-token
+    # draft + 12-token regenerated part; same weights as cfg2 (one draft model per system)
+    "draft_1b_recycle": dict(model="1b", dtype="bf16", n_audio=300, n_text=30,
+                             tree=dict(two_branch=(24, 12)), seed=1002),
 }
 
 _LAYER_MATS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
@@ -180,6 +184,19 @@ def random_tree(rng, n, max_children=2):
     return np.array(parents, np.int32)
 
 
+def two_branch_tree(len_old, len_new):
+    """Parent array of the draft model's recycling tree (Sec. IV-B): node 0 is the last verified
+    token; nodes 1..len_old chain below it (the previous draft, kept as sequence 1); nodes
+    len_old+1..len_old+len_new chain below node 0 as well (the part being regenerated, sequence
+    2).  The two branches never see each other."""
+    parents = [-1]
+    for i in range(len_old):
+        parents.append(i)                       # node i+1 hangs off node i
+    for i in range(len_new):
+        parents.append(0 if i == 0 else len_old + i)
+    return np.array(parents, np.int32)
+
+
 def make_tree(name, rng=None):
     """(parents, tokens) of a named workload's tree."""
     wl = WORKLOADS[name]
@@ -187,6 +204,8 @@ def make_tree(name, rng=None):
     rng = rng if rng is not None else np.random.default_rng([wl["seed"], 900020])
     if wl["tree"] == "cfg1":
         parents = tree_cfg1()
+    elif "two_branch" in wl["tree"]:
+        parents = two_branch_tree(*wl["tree"]["two_branch"])
     else:
         t = wl["tree"]
         parents, _, _ = sparse_tree(rng, t["trunk"], t["n_branches"], t["branch_depth"], t["rule"])
