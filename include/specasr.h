@@ -174,6 +174,26 @@ specasr_status specasr_tree_forward_top2(specasr_ctx *ctx, specasr_kv *kv, const
                                          int32_t *top2_dev, float *top1_prob_dev, float *logits_dev,
                                          void *workspace, size_t workspace_bytes, void *stream);
 
+/* Prefill (Sec. II-A: the audio embeddings produced by the speech encoder are prefilled alongside
+ * the text prompt; the verify rounds then run against that cache).  Appends n_pos[b] positions to
+ * every sequence b: position i takes the embedding row input_embeds[b][i] where use_embed[b][i] is
+ * non-zero, the token embedding of tokens[b][i] otherwise.  The positions are run through the
+ * decoder in chain-shaped chunks of at most max_nodes rows (a chain is the tree whose mask is the
+ * causal one), their K/V rows land in slots kv_len .. kv_len + n_pos - 1, and kv_len advances by
+ * n_pos.  The LM head runs only for the last chunk, and only if next_token is given.
+ *   tokens        HOST int32 [batch][max_pos], may be NULL if every position is an embedding
+ *   input_embeds  DEVICE [batch][max_pos][d_model] in config.dtype, with use_embed HOST uint8
+ *                 [batch][max_pos]; both NULL when every position is a token
+ *   n_pos         HOST int32 [batch], each 0..max_pos
+ *   next_token    optional HOST int32 [batch]: the model's greedy token after the last position
+ *                 (-1 for a sequence with n_pos = 0); when given the call synchronises the stream
+ * Errors: E_NULL, E_TREE (token id or n_pos out of range), E_KV_OVERFLOW, E_WORKSPACE; nothing is
+ * enqueued and kv_len is unchanged on error. */
+specasr_status specasr_prefill(specasr_ctx *ctx, specasr_kv *kv, const int32_t *tokens,
+                               const void *input_embeds, const uint8_t *use_embed,
+                               const int32_t *n_pos, int32_t max_pos, int32_t *next_token,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
 /* Stage: greedy acceptance (Sec. II-B: accept matching draft tokens, stop at the
  * first failure) from a DEVICE argmax array.  A draft node matches when its token
  * equals the argmax at its parent; the result is the deepest node whose whole

@@ -29,7 +29,7 @@ SPECASR_FLAG_NO_REPACK = 2
 SPECASR_MAX_NODES = 64
 
 EXPORTS = ("specasr_create", "specasr_destroy", "specasr_workspace_bytes", "specasr_verify_tree",
-           "specasr_tree_forward", "specasr_tree_forward_top2", "specasr_accept",
+           "specasr_tree_forward", "specasr_tree_forward_top2", "specasr_prefill", "specasr_accept",
            "specasr_accept_from_logits",
            "specasr_commit", "specasr_strerror", "specasr_last_hip_error", "specasr_abi_version",
            "specasr_uses_mfma", "specasr_profile_stage", "specasr_stage_time")
@@ -101,6 +101,9 @@ def load_library(path=None):
     lib.specasr_tree_forward_top2.restype = C.c_int
     lib.specasr_tree_forward_top2.argtypes = [vp, C.POINTER(specasr_kv), C.POINTER(specasr_tree), vp,
                                               vp, vp, vp, C.c_size_t, vp]
+    lib.specasr_prefill.restype = C.c_int
+    lib.specasr_prefill.argtypes = [vp, C.POINTER(specasr_kv), i32p, vp, C.POINTER(C.c_uint8), i32p,
+                                    C.c_int32, i32p, vp, C.c_size_t, vp]
     lib.specasr_accept.restype = C.c_int
     lib.specasr_accept.argtypes = [vp, C.POINTER(specasr_tree), C.c_int32, vp, vp, vp, vp, vp,
                                    C.c_size_t, vp]
@@ -245,6 +248,14 @@ def specasr_tree_forward_top2(ctx, kv, tree, top2_dev, top1_prob_dev, logits_dev
     return load_library().specasr_tree_forward_top2(ctx, C.byref(kv), C.byref(tree), _ptr(top2_dev),
                                                     _ptr(top1_prob_dev), _ptr(logits_dev),
                                                     _ptr(workspace), workspace_bytes, _ptr(stream))
+
+
+def specasr_prefill(ctx, kv, tokens, input_embeds, use_embed, n_pos, max_pos, next_token, workspace,
+                    workspace_bytes, stream=None):
+    ue = None if use_embed is None else use_embed.ctypes.data_as(C.POINTER(C.c_uint8))
+    return load_library().specasr_prefill(ctx, C.byref(kv), _i32(tokens), _ptr(input_embeds), ue,
+                                          _i32(n_pos), max_pos, _i32(next_token), _ptr(workspace),
+                                          workspace_bytes, _ptr(stream))
 
 
 def specasr_accept(ctx, tree, batch, argmax_dev, path_dev, accept_len_dev, next_token_dev,

@@ -7,6 +7,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <algorithm>
 #include <chrono>
 #include <vector>
 
@@ -328,6 +329,8 @@ struct ReadOut {
   float *logits = nullptr;
   int32_t *top2 = nullptr;
   float *prob = nullptr;
+  // nothing requested: the forward only fills the cache (all but the last chunk of a prefill)
+  bool none() const { return !argmax && !logits && !top2; }
 };
 
 // Steps 1-8 with the dtype-generic kernels.
@@ -361,6 +364,7 @@ void forward_generic(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, speca
     launch_swiglu(gu, R, F, t, st);
     launch_linear(dt, lw.w_down, d, F, t, F, x, d, R, true, st);
   }
+  if (ro.none()) return;
   launch_rmsnorm(dt, x, ctx->w.final_norm, R, d, md.rms_eps, h, st);
   launch_linear(dt, ctx->w.lm_head, V, d, h, d, lg, V, R, false, st);
   if (ro.top2)
@@ -475,6 +479,7 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
     pending = pl_dn.n_splits;
     pending_ld = pk.down.ldo;
   }
+  if (ro.none()) return;
   launch_residual_gain(x, part, pending, R, pending_ld, ctx->w.final_norm, d, hb, hb_lo, ssq, st);
   gemm_stage(ctx, SPECASR_STAGE_LM_HEAD, true, ctx->lm_head, hb, R, part, pl_lm, st);
   if (ro.top2)
@@ -789,6 +794,76 @@ specasr_status specasr_tree_forward_top2(specasr_ctx *ctx, specasr_kv *kv, const
     s = forward_common(ctx, &grp.kv, &grp.tree, ro, ws, L, hs, st);
     if (s != SPECASR_OK) return s;
   }
+  return SPECASR_OK;
+}
+
+specasr_status specasr_prefill(specasr_ctx *ctx, specasr_kv *kv, const int32_t *tokens,
+                               const void *input_embeds, const uint8_t *use_embed,
+                               const int32_t *n_pos, int32_t max_pos, int32_t *next_token,
+                               void *workspace, size_t workspace_bytes, void *stream) {
+  if (!ctx || !n_pos || (!tokens && !input_embeds)) return SPECASR_E_NULL;
+  if ((input_embeds == nullptr) != (use_embed == nullptr)) return SPECASR_E_NULL;
+  specasr_status s = check_kv(kv);
+  if (s != SPECASR_OK) return s;
+  const specasr_config &c = ctx->cfg;
+  const int B = kv->batch;
+  if (B > c.max_batch || max_pos < 1) return SPECASR_E_TREE;
+  for (int b = 0; b < B; ++b) {
+    if (n_pos[b] < 0 || n_pos[b] > max_pos) return SPECASR_E_TREE;
+    if (kv->kv_len[b] < 0 || (int64_t)kv->kv_len[b] + n_pos[b] > kv->capacity) return SPECASR_E_KV_OVERFLOW;
+    for (int i = 0; i < n_pos[b]; ++i) {
+      const size_t at = (size_t)b * max_pos + i;
+      if (use_embed && use_embed[at]) continue;
+      if (!tokens || tokens[at] < 0 || tokens[at] >= c.vocab) return SPECASR_E_TREE;
+    }
+  }
+  s = check_ws(ctx, workspace, workspace_bytes, B);
+  if (s != SPECASR_OK) return s;
+  hipStream_t st = (hipStream_t)stream;
+  char *ws = (char *)workspace;
+  const WsLayout L = ws_layout(ctx, B);
+  const size_t esz = c.dtype == SPECASR_BF16 ? 2 : 4;
+  const size_t seq_kv_bytes = (size_t)c.n_layers * c.n_kv_heads * (size_t)kv->capacity * c.head_dim * esz;
+  int32_t *argmax_dev = reinterpret_cast<int32_t *>(ws + L.outs);  // [max_nodes] of the current chunk
+  std::vector<int32_t> chunk_tok(c.max_nodes), chain(c.max_nodes);
+  for (int i = 0; i < c.max_nodes; ++i) chain[i] = i - 1;
+  std::vector<int32_t> kv_len_now(kv->kv_len, kv->kv_len + B);
+  bool any_result = false;
+  for (int b = 0; b < B; ++b) {
+    for (int c0 = 0; c0 < n_pos[b]; c0 += c.max_nodes) {
+      const int32_t n = std::min<int32_t>(c.max_nodes, n_pos[b] - c0);
+      const bool last = c0 + n == n_pos[b];
+      const size_t at = (size_t)b * max_pos + c0;
+      for (int i = 0; i < n; ++i) chunk_tok[i] = tokens ? tokens[at + i] : 0;
+      specasr_kv kvv{(char *)kv->k + (size_t)b * seq_kv_bytes, (char *)kv->v + (size_t)b * seq_kv_bytes,
+                     kv->capacity, 1, &kv_len_now[b]};
+      specasr_tree tv{chunk_tok.data(), chain.data(), &n,
+                      input_embeds ? (const char *)input_embeds + at * c.d_model * esz : nullptr,
+                      use_embed ? use_embed + at : nullptr};
+      HostStep hs;
+      build_step(ctx, &tv, 1, kvv.kv_len, &hs);
+      s = upload_meta(ctx, hs, ws, L, st);
+      if (s != SPECASR_OK) return s;
+      ReadOut ro;
+      if (last && next_token) ro.argmax = argmax_dev;
+      s = forward_common(ctx, &kvv, &tv, ro, ws, L, hs, st);
+      if (s != SPECASR_OK) return s;
+      kv_len_now[b] += n;  // a chain's rows already sit in slots kv_len .. kv_len+n-1, in order
+      if (last && next_token) {
+        s = ensure_staging(ctx);
+        if (s != SPECASR_OK) return s;
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->out_host + b, argmax_dev + (n - 1), 4, hipMemcpyDeviceToHost, st));
+        any_result = true;
+      }
+    }
+  }
+  if (any_result) {
+    HIP_TRY(ctx, hipStreamSynchronize(st));
+    for (int b = 0; b < B; ++b) next_token[b] = n_pos[b] > 0 ? ctx->out_host[b] : -1;
+  } else if (next_token) {
+    for (int b = 0; b < B; ++b) next_token[b] = -1;
+  }
+  for (int b = 0; b < B; ++b) kv->kv_len[b] = kv_len_now[b];
   return SPECASR_OK;
 }
 

@@ -148,6 +148,27 @@ class Verifier:
         torch.cuda.synchronize()
         return dict(status=rc, top2=top2, prob=prob, logits=logits)
 
+    def prefill(self, tokens, embeds=None, use_embed=None, want_next=True, stream=None):
+        """Append positions to every sequence: tokens = list (one per sequence) of int sequences,
+        embeds = optional device tensor [batch][max_pos][d_model], use_embed = list of flag lists.
+        Returns dict(status, next_token)."""
+        nb = self.batch
+        n_pos = np.asarray([len(t) for t in tokens], np.int32)
+        max_pos = int(embeds.shape[1]) if embeds is not None else max(1, int(n_pos.max()))
+        tok = np.zeros((nb, max_pos), np.int32)
+        ue = None
+        if use_embed is not None:
+            ue = np.zeros((nb, max_pos), np.uint8)
+        for b in range(nb):
+            tok[b, :n_pos[b]] = np.asarray(tokens[b], np.int32)
+            if ue is not None:
+                ue[b, :len(use_embed[b])] = use_embed[b]
+        nxt = np.full(nb, -7, np.int32) if want_next else None
+        rc = B.specasr_prefill(self.ctx, self._kv, tok, embeds, ue, n_pos, max_pos, nxt, self.ws_ptr,
+                               self.ws_bytes, stream)
+        torch.cuda.synchronize()
+        return dict(status=rc, next_token=nxt)
+
     def accept(self, tokens, parents, argmax_dev=None, logits_dev=None, stream=None):
         nb = len(tokens)
         tree, keep = self._tree(tokens, parents)

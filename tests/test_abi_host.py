@@ -158,3 +158,35 @@ def test_commit_path_validation(ctx):
     assert commit([], 4) == B.SPECASR_E_PATH
     assert commit([0, 1], 0) == B.SPECASR_E_TREE
     assert commit([0, 1], 4, kv_len=98) == B.SPECASR_E_KV_OVERFLOW
+
+
+def test_prefill_and_draft_forward_validate_on_the_host(ctx):
+    """specasr_prefill / specasr_tree_forward_top2: argument errors are found before anything is
+    enqueued (no GPU here), and kv_len is left alone."""
+    wsb = B.specasr_workspace_bytes(ctx, 1)
+    kvl = np.array([90], np.int32)
+    kv = B.make_kv(FAKE, FAKE, 100, kvl)
+    tok = np.zeros((1, 16), np.int32)
+    one = np.array([5], np.int32)
+    flags = np.zeros((1, 16), np.uint8)
+    nxt = np.zeros(1, np.int32)
+    assert B.specasr_prefill(ctx, kv, tok, None, None, None, 16, nxt, FAKE, wsb) == B.SPECASR_E_NULL
+    assert B.specasr_prefill(ctx, kv, None, None, None, one, 16, nxt, FAKE, wsb) == B.SPECASR_E_NULL
+    assert B.specasr_prefill(ctx, kv, tok, FAKE, None, one, 16, nxt, FAKE, wsb) == B.SPECASR_E_NULL
+    assert B.specasr_prefill(ctx, kv, tok, None, None, np.array([17], np.int32), 16, nxt, FAKE, wsb) == B.SPECASR_E_TREE
+    assert B.specasr_prefill(ctx, kv, tok, None, None, np.array([-1], np.int32), 16, nxt, FAKE, wsb) == B.SPECASR_E_TREE
+    assert B.specasr_prefill(ctx, kv, tok, None, None, np.array([11], np.int32), 16, nxt, FAKE, wsb) == B.SPECASR_E_KV_OVERFLOW
+    bad = tok.copy()
+    bad[0, 3] = 1000                                         # == vocab
+    assert B.specasr_prefill(ctx, kv, bad, None, None, one, 16, nxt, FAKE, wsb) == B.SPECASR_E_TREE
+    flags[0, 3] = 1                                          # ... but ignored where an embedding is used
+    assert B.specasr_prefill(ctx, kv, bad, FAKE, flags, one, 16, nxt, FAKE, 1024) == B.SPECASR_E_WORKSPACE
+    assert B.specasr_prefill(ctx, kv, tok, None, None, one, 16, nxt, None, wsb) == B.SPECASR_E_WORKSPACE
+    assert kvl[0] == 90
+    par, nn = np.full((1, 8), -1, np.int32), np.array([1], np.int32)
+    tree = B.make_tree(np.zeros((1, 8), np.int32), par, nn)
+    assert B.specasr_tree_forward_top2(ctx, kv, tree, None, FAKE, None, FAKE, wsb) == B.SPECASR_E_NULL
+    assert B.specasr_tree_forward_top2(ctx, kv, tree, FAKE, None, None, FAKE, wsb) == B.SPECASR_E_NULL
+    assert B.specasr_tree_forward_top2(ctx, kv, tree, FAKE, FAKE, None, FAKE, 1024) == B.SPECASR_E_WORKSPACE
+    kv2 = B.make_kv(FAKE, FAKE, 100, np.array([100], np.int32))
+    assert B.specasr_tree_forward_top2(ctx, kv2, tree, FAKE, FAKE, None, FAKE, wsb) == B.SPECASR_E_KV_OVERFLOW

@@ -94,29 +94,33 @@ def test_cfg2_1b_16_node_tree(model_1b):
 
 
 def test_cfg2_planted_trunk_and_library_prefill(model_1b):
-    """Prefix produced by the library itself (chain-tree prefill of 40 audio embeddings + 20 tokens),
-    then a tree whose trunk follows the oracle's greedy continuation: several drafts accepted."""
+    """Prefix produced by the library itself (specasr_prefill of config 2's 300 audio embeddings +
+    30 prompt tokens, six chain-shaped chunks), then a tree whose trunk follows the oracle's greedy
+    continuation: several drafts accepted."""
     cfg = model_1b.cfg
     om = model_1b.om
     rng = np.random.default_rng(2002)
-    n_a, n_t = 40, 20
+    spec = wl.WORKLOADS["cfg2_1b_n16"]
+    n_a, n_t = spec["n_audio"], spec["n_text"]
     audio = wl.bf16_to_f32(wl.bf16_bits(rng.standard_normal((n_a, cfg["d_model"])).astype(np.float32)))
     text = rng.integers(0, cfg["vocab"], n_t).astype(np.int32)
-    ver = model_1b.verifier(160)
     n = n_a + n_t
-    emb = torch.zeros((1, 64, cfg["d_model"]), dtype=torch.bfloat16, device=ver.device)
+    cap = n + 64
+    ver = model_1b.verifier(cap)
+    emb = torch.zeros((1, n, cfg["d_model"]), dtype=torch.bfloat16, device=ver.device)
     emb[0, :n_a] = torch.from_numpy(audio).to(ver.device).to(torch.bfloat16)
     tok = np.zeros(n, np.int32)
     tok[n_a:] = text
-    fw = ver.tree_forward([tok], [np.arange(-1, n - 1)], embeds=emb, use_embed=[[1] * n_a + [0] * n_t],
-                          want_logits=False)
-    assert fw["status"] == 0 and ver.commit([n], [list(range(n))]) == 0
-    kc, vc = om.empty_cache(160)
+    pf = ver.prefill([tok], embeds=emb, use_embed=[[1] * n_a + [0] * n_t])
+    assert pf["status"] == 0 and ver.kv_len[0] == n
+    kc, vc = om.empty_cache(cap)
     Lo, last = om.prefill(kc, vc, 0, audio.astype(np.float64), text)
     k1, v1 = ver.get_cache()
     for got, want in ((k1, kc), (v1, vc)):
         g = widen_cache(got[0, :, :, :n])
         assert np.abs(g - want[:, :, :n]).max() <= TOL_BF16 * np.abs(want[:, :, :n]).max()
+    if np.sort(last)[-1] - np.sort(last)[-2] > GAP:
+        assert pf["next_token"][0] == int(np.argmax(last))
     # greedy continuation from the oracle on the GPU's cache, 5 tokens
     kg, vg = widen_cache(k1[0]), widen_cache(v1[0])
     L, root, greedy = n, int(np.argmax(last)), []

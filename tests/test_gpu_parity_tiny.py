@@ -415,6 +415,62 @@ def test_chain_prefill_with_audio_embeddings(dtype, tol):
     ver.close()
 
 
+@pytest.mark.parametrize("dtype,tol,max_nodes", [("f32", TOL_F32, 16), ("bf16", TOL_BF16, 64),
+                                                 ("bf16", TOL_BF16, 24)])
+def test_prefill_entry_point_equals_oracle_prefill(dtype, tol, max_nodes):
+    """specasr_prefill on a batch of three sequences (audio embeddings then prompt tokens; lengths
+    that are not multiples of the chunk size; one sequence that already holds a prefix; one with
+    nothing to add): cache rows, kv_len and the greedy token after the last position equal the
+    oracle's prefill of each sequence alone."""
+    cfg = wl.MODELS["tiny"]
+    w = wl.make_weights(cfg, 97, dtype)
+    rng = np.random.default_rng(98)
+    cap, d = 192, cfg["d_model"]
+    om = oracle.OracleModel(cfg, w)
+    n_audio, n_text, L0 = [70, 0, 33], [41, 0, 9], [0, 12, 20]
+    nb, max_pos = 3, 120
+    ver = _verifier(cfg, w, dtype, max_nodes=max_nodes, capacity=cap, max_batch=nb)
+    K, V = wl.seeded_cache(cfg, 99, np.asarray(L0, np.int32), cap, dtype, batch=nb)
+    ver.set_cache(K, V, L0)
+    emb = torch.zeros((nb, max_pos, d), dtype=ver.tdtype, device=ver.device)
+    toks, flags, audio = [], [], []
+    for b in range(nb):
+        a = rng.standard_normal((n_audio[b], d)).astype(np.float32)
+        if dtype == "bf16":
+            a = wl.bf16_to_f32(wl.bf16_bits(a))
+        audio.append(a)
+        emb[b, :n_audio[b]] = torch.from_numpy(a).to(ver.device).to(ver.tdtype)
+        text = rng.integers(0, cfg["vocab"], n_text[b]).astype(np.int32)
+        toks.append(np.concatenate([np.zeros(n_audio[b], np.int32), text]))
+        flags.append([1] * n_audio[b] + [0] * n_text[b])
+    out = ver.prefill(toks, embeds=emb, use_embed=flags)
+    assert out["status"] == 0
+    k1, v1 = ver.get_cache()
+    for b in range(nb):
+        n = n_audio[b] + n_text[b]
+        assert ver.kv_len[b] == L0[b] + n
+        kc, vc = widen_cache(K[b]).copy(), widen_cache(V[b]).copy()
+        L, last = om.prefill(kc, vc, L0[b], audio[b].astype(np.float64), toks[b][n_audio[b]:], chunk=max_nodes)
+        assert L == L0[b] + n
+        if n == 0:
+            assert out["next_token"][b] == -1
+            assert np.array_equal(k1[b], K[b]) and np.array_equal(v1[b], V[b])
+            continue
+        for got, want, before in ((k1[b], kc, K[b]), (v1[b], vc, V[b])):
+            g = widen_cache(got[:, :, L0[b]:L])
+            assert np.abs(g - want[:, :, L0[b]:L]).max() <= tol * np.abs(want[:, :, L0[b]:L]).max()
+            assert np.array_equal(got[:, :, :L0[b]], before[:, :, :L0[b]])   # the old prefix is untouched
+        srt = np.sort(last)
+        if srt[-1] - srt[-2] > 0.05:
+            assert out["next_token"][b] == int(np.argmax(last))
+    # error paths enqueue nothing: overflow and a bad token id leave kv_len alone
+    before = ver.kv_len.copy()
+    assert ver.prefill([[1] * 200, [], []])["status"] == -4
+    assert ver.prefill([[cfg["vocab"]], [], []])["status"] == -3
+    assert np.array_equal(ver.kv_len, before)
+    ver.close()
+
+
 @pytest.mark.parametrize("shape", [
     dict(n_heads=4, n_kv_heads=2, head_dim=64),     # grouped-query, 2 query heads per KV head
     dict(n_heads=8, n_kv_heads=1, head_dim=64, d_model=512),   # 8 query heads on one KV head
