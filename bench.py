@@ -56,6 +56,74 @@ def cpu_baseline(cfg, w_host, kc, vc, kv_len, tokens, parents, reps, draft=False
     return spent / reps, spent, oracle.num_threads()
 
 
+def bench_prefill(args, spec, cfg, w_host, ver, stage_id, t_gen, log):
+    """Times specasr_prefill of the workload's prefix: n_audio seeded audio-embedding rows followed
+    by n_text seeded prompt tokens, appended to an empty cache in chain-shaped chunks of 64."""
+    import numpy as np
+    import torch
+    import workload as wl
+    from paper_2507_18181_amd import binding as B
+    n_a, n_t = spec["n_audio"], spec["n_text"]
+    T = n_a + n_t
+    audio, text = wl.make_prefix_inputs(cfg, spec["seed"], n_a, n_t)
+    audio = wl.bf16_to_f32(wl.bf16_bits(audio.astype(np.float32)))
+    emb = torch.zeros((1, T, cfg["d_model"]), dtype=torch.bfloat16, device="cuda:0")
+    emb[0, :n_a] = torch.from_numpy(audio).to("cuda:0").to(torch.bfloat16)
+    tok = np.zeros(T, np.int32)
+    tok[n_a:] = text
+    flags = [[1] * n_a + [0] * n_t]
+
+    def step():
+        ver.kv_len[0] = 0
+        out = ver.prefill([tok], embeds=emb, use_embed=flags)
+        assert out["status"] == 0 and ver.kv_len[0] == T
+        return out
+
+    steps, warm = max(1, args.steps // 5), max(1, args.warmup // 5)
+    log("prefill warm-up")
+    for _ in range(warm):
+        step()
+    assert B.specasr_profile_stage(ver.ctx, stage_id, True) == 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    rc, stage_ms, stage_launches, stage_bytes = B.specasr_stage_time(ver.ctx)
+    B.specasr_profile_stage(ver.ctx, stage_id, False)
+    kern_ms = stage_ms / max(1, stage_launches)
+    kern_gbs = stage_bytes / (kern_ms * 1e-3) / 1e9
+    result = {
+        "metric": "prefill_positions_per_s", "value": round(T * steps / dt, 1), "unit": "positions/s",
+        "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": round(dt / steps * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": args.workload + " (prefix prefill)", "model": spec["model"],
+                   "audio_positions": n_a, "prompt_tokens": n_t, "chunk": 64, "batch": 1},
+        "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel (%s projection, 64 rows)" % args.stage,
+                     "achieved": round(kern_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(kern_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "launches_timed": stage_launches, "avg_launch_us": round(kern_ms * 1e3, 2),
+                     "bytes_per_launch": stage_bytes},
+        "weights_gen_s": round(t_gen, 1),
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        log("timing the CPU oracle on the first chunk")
+        om = oracle.OracleModel(cfg, w_host)
+        kc, vc = om.empty_cache(64)
+        t1 = time.perf_counter()
+        om.prefill(kc, vc, 0, audio[:64].astype(np.float64), np.zeros(0, np.int32))
+        spent = time.perf_counter() - t1
+        result["cpu_baseline"] = {
+            "value": round(64 / spent, 2), "unit": "positions/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": "fp64 oracle prefill of the first 64 of the %d positions (one chunk, all %d "
+                      "layers) = %.1f s of CPU work" % (T, cfg["n_layers"], spent)}
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -68,6 +136,9 @@ def main():
                     help="also run one plain 1 GiB device copy (a kernel of known traffic, for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--stage", default="gate_up", choices=["qkv", "o", "gate_up", "down", "lm_head"])
+    ap.add_argument("--prefill", action="store_true",
+                    help="time specasr_prefill of the workload's prefix (audio embeddings + prompt "
+                         "tokens into an empty cache) instead of the verify step")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU only (the verify step of one utterance on one "
@@ -108,6 +179,10 @@ def main():
     torch.cuda.synchronize()
 
     stage_id = ["qkv", "o", "gate_up", "down", "lm_head"].index(args.stage)
+    if args.prefill:
+        bench_prefill(args, spec, cfg, w_host, ver, stage_id, t_gen, log)
+        ver.close()
+        return
 
     draft = isinstance(spec["tree"], dict) and "two_branch" in spec["tree"]
 
