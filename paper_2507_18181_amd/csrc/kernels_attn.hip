@@ -327,9 +327,10 @@ __global__ void tree_attention_merge_kernel(StepMeta m, int H, int HD, int chunk
 
 template <int HD>
 static void launch_attn_hd(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
-                           int max_seq_nodes, int chunk_keys, int n_chunks, const uint16_t *qb,
-                           const uint16_t *qb_lo, const void *kc, const void *vc, float *o_part,
-                           float *ml_part, uint16_t *out, uint16_t *out_lo, hipStream_t st) {
+                           int max_seq_nodes, int chunk_keys, int n_chunks, bool pair,
+                           const uint16_t *qb, const uint16_t *qb_lo, const void *kc, const void *vc,
+                           float *o_part, float *ml_part, uint16_t *out, uint16_t *out_lo,
+                           hipStream_t st) {
   const int G = md.n_heads / md.n_kv_heads;
   const int row_groups = (G * max_seq_nodes + 31) / 32;
   // LDS: 4 wavefronts x 2 V tiles, reused for the merge (4 x RGW x HD/32 x 4 KB + (m, l))
@@ -338,8 +339,7 @@ static void launch_attn_hd(const StepMeta &m, const ModelDims &md, const KvGeom 
     const size_t mg = (size_t)4 * rgw * (HD / 32) * 4096 + (size_t)4 * rgw * 32 * 2 * 4;
     return vt > mg ? vt : mg;
   };
-  // two row groups per workgroup only where their accumulators fit the register file (head_dim 64)
-  if (row_groups <= 1 || HD > 64) {
+  if (!pair || HD > 64) {
     dim3 grid((n_chunks * md.n_kv_heads + 7) / 8 * 8 * row_groups, 1, m.batch);
     tree_attention_kernel<HD, 1><<<grid, 256, lds_bytes(1), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, row_groups, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, n_chunks, o_part, ml_part);
   } else {
@@ -384,13 +384,19 @@ void launch_tree_attention(const StepMeta &m, const ModelDims &md, const KvGeom 
                            float *ml_part, uint16_t *out, uint16_t *out_lo, hipStream_t st) {
   const int G = md.n_heads / md.n_kv_heads;
   const int row_groups = (G * max_seq_nodes + 31) / 32;
-  const int n_rgb = (row_groups <= 1 || md.head_dim > 64) ? row_groups : (row_groups + 1) / 2;
+  // Two query row groups per workgroup halve the key traffic, but only where their accumulators
+  // fit the register file (head_dim 64) and the key range is long enough to matter: with at most
+  // one tile per wavefront a second row group would just run behind the first on the same
+  // wavefront.
+  bool pair = row_groups > 1 && md.head_dim <= 64;
+  if (pair && tree_attention_chunk_keys(max_total_keys, md.n_kv_heads, m.batch, row_groups) <= 128) pair = false;
+  const int n_rgb = pair ? (row_groups + 1) / 2 : row_groups;
   const int ck = tree_attention_chunk_keys(max_total_keys, md.n_kv_heads, m.batch, n_rgb);
   const int n_chunks = (max_total_keys + ck - 1) / ck;
   if (md.head_dim == 64)
-    launch_attn_hd<64>(m, md, g, layer, max_seq_nodes, ck, n_chunks, qb, qb_lo, kc, vc, o_part, ml_part, out, out_lo, st);
+    launch_attn_hd<64>(m, md, g, layer, max_seq_nodes, ck, n_chunks, pair, qb, qb_lo, kc, vc, o_part, ml_part, out, out_lo, st);
   else
-    launch_attn_hd<128>(m, md, g, layer, max_seq_nodes, ck, n_chunks, qb, qb_lo, kc, vc, o_part, ml_part, out, out_lo, st);
+    launch_attn_hd<128>(m, md, g, layer, max_seq_nodes, ck, n_chunks, pair, qb, qb_lo, kc, vc, o_part, ml_part, out, out_lo, st);
 }
 
 }  // namespace specasr
