@@ -92,9 +92,11 @@ size_t meta_words(int rows_max, int batch) {
 inline int pad32(int v) { return (v + 31) / 32 * 32; }
 
 // Chooses the k-split S of one skinny GEMM (workgroup g takes chunk g % S and every (P/S)-th
-// band).  Cost model fitted to measurements on MI355X, in microseconds per wavefront: 0.33 per
-// weight tile streamed, 0.45 per band (cross-wavefront reduction and partial write), 0.34 per
-// k-step of activations loaded into registers.  The slice of a wavefront must fit its ring.
+// band).  Cost model fitted to measurements on MI355X, in microseconds per wavefront: per weight
+// tile streamed, per band (cross-wavefront reduction and partial write) and per k-step of
+// activations loaded into registers -- 0.33 / 0.45 / 0.34 with one node group, 0.23 / 1.49 / 0.22
+// with two (twice the accumulators to sum and store per band).  The slice of a wavefront must
+// fit its ring.
 GemmPlan plan_gemm(int n_bands, int ksteps, int nb, int n_cu) {
   GemmPlan best;
   double best_cost = 1e300;
@@ -105,7 +107,8 @@ GemmPlan plan_gemm(int n_bands, int ksteps, int nb, int n_cu) {
     const int len = (chunk + 7) / 8;  // k-steps of the longest wavefront slice
     if (len > lw_max) continue;
     const int units = (n_bands + n_cu / S - 1) / (n_cu / S);
-    const double cost = 0.33 * units * len + 0.45 * units + 0.34 * nb * len;
+    const double cost = nb == 1 ? 0.33 * units * len + 0.45 * units + 0.34 * len
+                                : 0.23 * units * len + 1.49 * units + 0.22 * len;
     if (cost < best_cost) {
       best_cost = cost;
       best.n_splits = S;
