@@ -53,6 +53,10 @@ typedef struct {
 
 /* ---- storage widening ---------------------------------------------------- */
 
+/* Value a cache of storage type `dtype` holds after `v` is written to it: nearest fp32 for an
+ * fp32 cache, nearest bf16 (ties to even, taken from that fp32) for a bf16 cache. */
+static double store_round(double v, int dtype);
+
 static double bf16_bits_to_double(uint16_t b) {
   uint32_t u = ((uint32_t)b) << 16;
   float f;
@@ -153,6 +157,17 @@ int oracle_tree_meta(const int32_t *parents, int n, int32_t *depth, uint8_t *anc
   return 0;
 }
 
+static double store_round(double v, int dtype) {
+  if (dtype == ORACLE_F64) return v;
+  float f = (float)v;
+  if (dtype == ORACLE_F32) return (double)f;
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  if ((u & 0x7f800000u) == 0x7f800000u) return (double)f; /* inf / nan unchanged */
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return bf16_bits_to_double((uint16_t)(u >> 16));
+}
+
 /* ---- steps 1-8: decoder forward over the tree tokens ----------------------
  *
  * kcache/vcache : [n_layers][n_kv_heads][capacity][head_dim], storage cdtype;
@@ -164,9 +179,12 @@ int oracle_tree_meta(const int32_t *parents, int n, int32_t *depth, uint8_t *anc
  * Outputs (any may be NULL):
  *   logits [n][vocab], amax[n] (lowest index on exact ties),
  *   ktree/vtree [n_layers][n_kv_heads][n][head_dim]: the K (post-RoPE) and V
- *   rows computed for each node, indexed by node.
+ *   rows computed for each node, indexed by node, as the cache holds them.
  * Node i is evaluated at position L + depth[i]; it attends to cache slots
- * [0, L) and to the tree nodes on its own root path.
+ * [0, L) and to the tree nodes on its own root path.  The K/V rows of the tree
+ * nodes are cache entries too (slot L + node): they take the cache's storage
+ * type before attention reads them, like every other slot (no-op for an fp64
+ * cache).
  */
 int oracle_tree_forward(const oracle_config *cfg, const oracle_weights *w, const void *kcache,
                         const void *vcache, int cdtype, int64_t capacity, int64_t L,
@@ -226,6 +244,11 @@ int oracle_tree_forward(const oracle_config *cfg, const oracle_weights *w, const
       int64_t pos = L + depth[i];
       for (int a = 0; a < H; ++a) oracle_rope(q + (size_t)i * dq + (size_t)a * hd, hd, pos, cfg->rope_theta);
       for (int b = 0; b < Hkv; ++b) oracle_rope(k + (size_t)i * dkv + (size_t)b * hd, hd, pos, cfg->rope_theta);
+    }
+    /* the rows are appended to the cache: they take its storage type */
+    for (size_t e = 0; e < (size_t)n * dkv; ++e) {
+      k[e] = store_round(k[e], cdtype);
+      v[e] = store_round(v[e], cdtype);
     }
     if (ktree && vtree) {
       for (int b = 0; b < Hkv; ++b)

@@ -230,6 +230,25 @@ def test_cfg3_7b_32_node_tree(model_7b):
     ver.close()
 
 
+def test_cfg6_13b_32_node_tree():
+    """13B-class target (40 layers, d 5120, 40 heads of 128, FFN 13824): shapes that are not powers
+    of two in any dimension (320 k-steps, 432 FFN bands, 40 KV heads); config 3's prefix and tree."""
+    from paper_2507_18181_amd import binding as B
+    spec = wl.WORKLOADS["cfg6_13b_n32"]
+    m = _Model("13b", spec["seed"])
+    L = spec["n_audio"] + spec["n_text"]
+    parents, tokens = wl.make_tree("cfg6_13b_n32")
+    assert len(parents) == 32
+    ver = m.verifier(L + 64)
+    assert B.specasr_uses_mfma(ver.ctx, 32) == 1
+    K, V = wl.seeded_cache(m.cfg, spec["seed"], L, L + 64, "bf16")
+    ver.set_cache(K, V, [L])
+    _round_checks(ver, m.om, tokens, parents, L)
+    ver.close()
+    del m
+    torch.cuda.empty_cache()
+
+
 def test_cfg5_7b_long_prefix_64_nodes_20_rounds(model_7b):
     """Long-utterance stress: prefix 3200, 64-node trees (trunk 24 + 8 depth-5 branches), 20 rounds.
     Each round runs the model forward, takes acceptance from SEEDED logits (planted targets) through

@@ -297,7 +297,7 @@ def test_gqa_equals_mha_with_replicated_kv_heads():
 
 
 def test_storage_dtypes_are_widened_exactly():
-    """bf16-bit weights == the same values held as float32; f32 cache == f64 cache."""
+    """bf16-bit weights give exactly the results of the same values held as float32."""
     cfg = dict(TINY)
     wb = wl.make_weights(cfg, 27, "bf16")
     wf = {k: (wl.bf16_to_f32(v) if k != "layers" else None) for k, v in wb.items()}
@@ -311,15 +311,43 @@ def test_storage_dtypes_are_widened_exactly():
         kc, vc = om.empty_cache(16)
         L, _ = om.prefill(kc, vc, 0, None, np.array([3, 1, 4], np.int32))
         res.append(om.tree_forward(kc, vc, L, tokens, parents)["logits"])
-        kc32, vc32 = kc.astype(np.float32), vc.astype(np.float32)
-        a = om.tree_forward(kc32, vc32, L, tokens, parents)["logits"]
-        b = om.tree_forward(kc32.astype(np.float64), vc32.astype(np.float64), L, tokens, parents)["logits"]
-        assert np.array_equal(a, b)
-        kb, vb = wl.bf16_bits(kc32), wl.bf16_bits(vc32)
-        a = om.tree_forward(kb, vb, L, tokens, parents)["logits"]
-        b = om.tree_forward(wl.bf16_to_f32(kb), wl.bf16_to_f32(vb), L, tokens, parents)["logits"]
-        assert np.array_equal(a, b)
     assert np.array_equal(res[0], res[1])
+
+
+def test_tree_rows_take_the_cache_storage_type():
+    """The K/V rows of the tree nodes are cache entries (slot L + node): over an f32 or bf16 cache
+    they are rounded to that type before attention reads them.  (a) The first layer's rows equal
+    an independent rounding of the fp64 rows (inputs of layer 0 do not depend on the cache
+    type).  (b) Consequence: a chain evaluated in one pass over a bf16 cache equals node-by-node
+    decoding that writes each row into the bf16 cache and reads it back -- the property that
+    makes tree verification equal to sequential decoding through a real cache."""
+    cfg = dict(TINY)
+    w = _boost(wl.make_weights(cfg, 28, "f32"), 4.0)
+    om = oracle.OracleModel(cfg, w)
+    rng = np.random.default_rng(11)
+    L, cap, n = 5, 16, 6
+    kc, vc = om.empty_cache(cap)
+    om.prefill(kc, vc, 0, None, rng.integers(0, cfg["vocab"], L).astype(np.int32))
+    kb, vb = wl.bf16_bits(kc.astype(np.float32)), wl.bf16_bits(vc.astype(np.float32))
+    k64, v64 = wl.bf16_to_f32(kb).astype(np.float64), wl.bf16_to_f32(vb).astype(np.float64)
+    tokens = rng.integers(0, cfg["vocab"], n).astype(np.int32)
+    chain = np.arange(-1, n - 1, dtype=np.int32)
+    r64 = om.tree_forward(k64, v64, L, tokens, chain)
+    rb = om.tree_forward(kb, vb, L, tokens, chain)
+    r32 = om.tree_forward(k64.astype(np.float32), v64.astype(np.float32), L, tokens, chain)
+    for name in ("ktree", "vtree"):
+        want = wl.bf16_to_f32(wl.bf16_bits(r64[name][0].astype(np.float32))).astype(np.float64)
+        assert np.array_equal(rb[name][0], want)
+        assert np.array_equal(r32[name][0], r64[name][0].astype(np.float32).astype(np.float64))
+        assert not np.array_equal(rb[name][0], r64[name][0])
+    # (b) node by node through the bf16 cache
+    kk, vv = kb.copy(), vb.copy()
+    for i in range(n):
+        r = om.tree_forward(kk, vv, L + i, tokens[i:i + 1], np.array([-1], np.int32))
+        kk[:, :, L + i] = wl.bf16_bits(r["ktree"][:, :, 0].astype(np.float32))
+        vv[:, :, L + i] = wl.bf16_bits(r["vtree"][:, :, 0].astype(np.float32))
+        assert np.allclose(r["logits"][0], rb["logits"][i], rtol=1e-9, atol=1e-11)
+    assert not np.allclose(r64["logits"][n - 1], rb["logits"][n - 1], rtol=1e-9, atol=1e-11)
 
 
 # --------------------------------------------------------------------------- acceptance
@@ -430,7 +458,8 @@ def test_commit_equals_prefill_of_accepted_tokens():
 
 def test_workload_tree_shapes():
     """Node counts of the named workloads: 6+2, 12+2*2, 16+4*4, 16+2*4, 24+8*5."""
-    want = dict(cfg1_tiny=8, cfg2_1b_n16=16, cfg3_7b_n32=32, cfg4_1b_b16=24, cfg5_7b_n64=64)
+    want = dict(cfg1_tiny=8, cfg2_1b_n16=16, cfg3_7b_n32=32, cfg4_1b_b16=24, cfg5_7b_n64=64,
+                cfg6_13b_n32=32)
     for name, n in want.items():
         parents, tokens = wl.make_tree(name)
         assert len(parents) == n == len(tokens)

@@ -22,6 +22,9 @@ MODELS = {
     # Llama-7B-class
     "7b": dict(n_layers=32, d_model=4096, n_heads=32, n_kv_heads=32, head_dim=128, d_ffn=11008,
                vocab=32000, rms_eps=1e-5, rope_theta=10000.0),
+    # Llama/Vicuna-13B-class (the largest target of Sec. V-A)
+    "13b": dict(n_layers=40, d_model=5120, n_heads=40, n_kv_heads=40, head_dim=128, d_ffn=13824,
+                vocab=32000, rms_eps=1e-5, rope_theta=10000.0),
 }
 
 # name -> (model, dtype, n_audio, n_text, tree recipe, base seed)
@@ -39,6 +42,10 @@ WORKLOADS = {
     "cfg5_7b_n64": dict(model="7b", dtype="bf16", n_audio=3000, n_text=200, rounds=20,
                         tree=dict(trunk=24, n_branches=8, branch_depth=5, rule="lowest"),
                         seed=1005),
+    # the 13B-class target on config 3's prefix and tree shape
+    "cfg6_13b_n32": dict(model="13b", dtype="bf16", n_audio=750, n_text=60,
+                         tree=dict(trunk=16, n_branches=4, branch_depth=4, rule="lowest"),
+                         seed=1006),
     # draft side (Sec. IV-B): the 1.1B-class draft model on the recycling tree, previous 24-token
     # draft + 12-token regenerated part; same weights as cfg2 (one draft model per system)
     "draft_1b_recycle": dict(model="1b", dtype="bf16", n_audio=300, n_text=30,
