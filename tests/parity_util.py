@@ -8,6 +8,10 @@ import workload as wl
 TOL_F32 = 1e-4     # fp32 storage, fp32 arithmetic on the GPU vs fp64 oracle
 TOL_BF16 = 2e-2    # bf16 storage and bf16 MFMA operands (stated by the benchmark spec)
 GAP = 0.05         # argmax must agree wherever the oracle's top-2 logit gap exceeds this
+# The stated tolerance leaves two orders of magnitude of room (measured: <= 2.3e-4 on every bf16
+# config, 1.1B to 13B).  A tenth of it is asserted as well, so that a loss of precision in a
+# kernel shows up long before the stated bound is reached.
+GUARD_BF16 = 2e-3
 
 
 def row_rel_err(g, o):
@@ -35,6 +39,8 @@ def check_forward(ref, gpu_logits, gpu_argmax, tol):
     err = row_rel_err(gpu_logits[:n], ref["logits"])
     print("logit rel err: max %.3e mean %.3e (tol %g, %d rows)" % (err.max(), err.mean(), tol, n))
     assert err.max() <= tol, "logit rel err %s > %g" % (err, tol)
+    if tol == TOL_BF16:
+        assert err.max() <= GUARD_BF16, "logit rel err %s above the regression guard %g" % (err, GUARD_BF16)
     dec = top2_gap(ref["logits"]) > GAP
     assert np.array_equal(np.asarray(gpu_argmax[:n])[dec], ref["amax"][dec])
     return dec
