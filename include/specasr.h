@@ -17,7 +17,8 @@
  *    pointers are ordinary host memory.  The caller owns every buffer it passes
  *    (weights, KV cache, workspace, logits); they are borrowed for the call, the
  *    weights for the life of the context.  The library allocates device memory
- *    only inside specasr_create (optional repacked weight copy, small tables).
+ *    only inside specasr_create (the optional repacked weight copy) and a few KB
+ *    of pinned host staging memory on the first call that needs it.
  *  - `stream` is a raw hipStream_t (NULL = the default stream).
  *  - All validation happens on the host before anything is enqueued: a call that
  *    returns an error has not touched the cache, kv_len or any output.
@@ -128,9 +129,8 @@ typedef struct specasr_ctx specasr_ctx;
 
 /* Create a context for one model on the current HIP device.  Validates the
  * configuration (E_CONFIG), may copy weights into a streaming-friendly layout
- * unless SPECASR_FLAG_NO_REPACK (values unchanged bit for bit), allocates small
- * tables and pinned staging buffers.  The weight pointers must stay valid until
- * specasr_destroy. */
+ * unless SPECASR_FLAG_NO_REPACK (values unchanged bit for bit).  The weight
+ * pointers must stay valid until specasr_destroy. */
 specasr_status specasr_create(const specasr_config *cfg, const specasr_weights *weights,
                               specasr_ctx **out);
 void specasr_destroy(specasr_ctx *ctx);
