@@ -270,6 +270,39 @@ def test_draft_readout_two_branch_tree(dtype, flags, tol):
     ver.close()
 
 
+def test_calls_on_a_caller_stream_give_the_same_results():
+    """Every entry point takes a raw hipStream_t: a round enqueued on a non-default stream (with
+    the cache upload ordered before it) equals the same round on the default stream."""
+    cfg = wl.MODELS["tiny"]
+    w = wl.make_weights(cfg, 61, "bf16")
+    rng = np.random.default_rng(62)
+    L, cap = 50, 128
+    K, V = wl.seeded_cache(cfg, 63, L, cap, "bf16")
+    parents = wl.random_tree(rng, 40)
+    tokens = wl.tree_tokens(rng, parents, cfg["vocab"])
+    ver = _verifier(cfg, w, "bf16", max_nodes=64, capacity=cap)
+    ver.set_cache(K, V, [L])
+    ref = ver.verify_tree([tokens], [parents], want_logits=True)
+    k_ref, v_ref = ver.get_cache()
+    stream = torch.cuda.Stream()
+    ver.set_cache(K, V, [L])
+    torch.cuda.synchronize()
+    out = ver.verify_tree([tokens], [parents], want_logits=True, stream=stream.cuda_stream)
+    stream.synchronize()
+    assert out["status"] == 0
+    for key in ("argmax", "path", "accept_len", "next_token"):
+        assert np.array_equal(out[key], ref[key]), key
+    assert torch.equal(out["logits"], ref["logits"])
+    k2, v2 = ver.get_cache()
+    assert np.array_equal(k2, k_ref) and np.array_equal(v2, v_ref)
+    ver.set_cache(K, V, [L])
+    torch.cuda.synchronize()
+    top = ver.tree_forward_top2([tokens], [parents], stream=stream.cuda_stream)
+    stream.synchronize()
+    assert np.array_equal(top["top2"][0, :40, 0].cpu().numpy(), ref["argmax"][0, :40])
+    ver.close()
+
+
 def test_accept_stage_bit_exact_against_oracle():
     """Acceptance from device argmax arrays and from logits, random trees with tiny vocabularies
     (many matches, duplicate sibling tokens), batch of 5, sizes 1..64."""
