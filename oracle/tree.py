@@ -215,15 +215,27 @@ class OracleModel:
     # -- step 10: commit = gather the accepted nodes' rows behind the prefix --
     @staticmethod
     def commit(kc, vc, L, ktree, vtree, path):
-        """Write rows L+k <- node path[k] (fp64 caches only); returns the new length."""
-        assert kc.dtype == np.float64
+        """Write rows L+k <- node path[k]; returns the new length.  The rows come from a forward
+        over this very cache, so they already hold values of its storage type (fp64, fp32, or
+        bf16 bit patterns in uint16): the conversion below is exact, and checked to be."""
+        def stored(rows):
+            if kc.dtype == np.float64:
+                return rows
+            f32 = rows.astype(np.float32)
+            assert np.array_equal(f32.astype(np.float64), rows), "rows not representable in fp32"
+            if kc.dtype == np.float32:
+                return f32
+            assert kc.dtype == np.uint16
+            bits = np.ascontiguousarray(f32).view(np.uint32)
+            assert not np.any(bits & np.uint32(0xFFFF)), "rows not representable in bf16"
+            return (bits >> np.uint32(16)).astype(np.uint16)
         for k, node in enumerate(path):
-            kc[:, :, L + k, :] = ktree[:, :, node, :]
-            vc[:, :, L + k, :] = vtree[:, :, node, :]
+            kc[:, :, L + k, :] = stored(ktree[:, :, node, :])
+            vc[:, :, L + k, :] = stored(vtree[:, :, node, :])
         return L + len(path)
 
     def prefill(self, kc, vc, L, embeds, tokens, chunk=64):
-        """Extend an fp64 cache by a chain of inputs: first the rows of ``embeds``
+        """Extend a cache (any storage type) by a chain of inputs: first the rows of ``embeds``
         ([A,d] audio-embedding vectors, may be empty), then ``tokens``.  A chain is
         the tree in which every node's parent is its predecessor, so this is plain
         causal prefill.  Returns (new length, logits of the last position)."""

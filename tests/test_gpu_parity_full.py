@@ -113,12 +113,13 @@ def test_cfg2_planted_trunk_and_library_prefill(model_1b):
     tok[n_a:] = text
     pf = ver.prefill([tok], embeds=emb, use_embed=[[1] * n_a + [0] * n_t])
     assert pf["status"] == 0 and ver.kv_len[0] == n
-    kc, vc = om.empty_cache(cap)
+    kc, vc = om.empty_cache(cap, np.uint16)          # bf16 storage, like the GPU's cache
     Lo, last = om.prefill(kc, vc, 0, audio.astype(np.float64), text)
     k1, v1 = ver.get_cache()
     for got, want in ((k1, kc), (v1, vc)):
-        g = widen_cache(got[0, :, :, :n])
-        assert np.abs(g - want[:, :, :n]).max() <= TOL_BF16 * np.abs(want[:, :, :n]).max()
+        g, wv = widen_cache(got[0, :, :, :n]), widen_cache(want[:, :, :n])
+        # rounded rows on both sides: one bf16 step (2^-8 of an element) plus the arithmetic difference
+        assert np.abs(g - wv).max() <= 5e-3 * np.abs(wv).max()
     if np.sort(last)[-1] - np.sort(last)[-2] > GAP:
         assert pf["next_token"][0] == int(np.argmax(last))
     # greedy continuation from the oracle on the GPU's cache, 5 tokens

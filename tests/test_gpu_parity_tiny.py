@@ -482,16 +482,19 @@ def test_prefill_entry_point_equals_oracle_prefill(dtype, tol, max_nodes):
     for b in range(nb):
         n = n_audio[b] + n_text[b]
         assert ver.kv_len[b] == L0[b] + n
-        kc, vc = widen_cache(K[b]).copy(), widen_cache(V[b]).copy()
+        kc, vc = K[b].copy(), V[b].copy()         # the oracle prefills a cache of the same storage type
         L, last = om.prefill(kc, vc, L0[b], audio[b].astype(np.float64), toks[b][n_audio[b]:], chunk=max_nodes)
         assert L == L0[b] + n
         if n == 0:
             assert out["next_token"][b] == -1
             assert np.array_equal(k1[b], K[b]) and np.array_equal(v1[b], V[b])
             continue
+        # bf16: both sides store rounded rows, so elements may differ by one bf16 step (2^-8 of
+        # the element) on top of the arithmetic difference
+        row_tol = tol if dtype == "f32" else 5e-3
         for got, want, before in ((k1[b], kc, K[b]), (v1[b], vc, V[b])):
-            g = widen_cache(got[:, :, L0[b]:L])
-            assert np.abs(g - want[:, :, L0[b]:L]).max() <= tol * np.abs(want[:, :, L0[b]:L]).max()
+            g, wv = widen_cache(got[:, :, L0[b]:L]), widen_cache(want[:, :, L0[b]:L])
+            assert np.abs(g - wv).max() <= row_tol * np.abs(wv).max()
             assert np.array_equal(got[:, :, :L0[b]], before[:, :, :L0[b]])   # the old prefix is untouched
         srt = np.sort(last)
         if srt[-1] - srt[-2] > 0.05:
