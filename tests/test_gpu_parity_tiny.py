@@ -535,3 +535,35 @@ def test_attention_shapes_bf16(shape):
         k1, v1 = ver.get_cache()
         check_tree_kv(k1[0], v1[0], L, ref, TOL_BF16)
     ver.close()
+
+
+@pytest.mark.parametrize("shape", [
+    dict(d_model=48, d_ffn=80, n_heads=1, n_kv_heads=1, head_dim=64, vocab=97),      # 3 k-steps: fewer than wavefronts
+    dict(d_model=272, d_ffn=1008, n_heads=4, n_kv_heads=2, head_dim=64, vocab=1003),  # 17 / 63 k-steps, 31.5 FFN bands
+    dict(d_model=1040, d_ffn=2064, n_heads=8, n_kv_heads=2, head_dim=128, vocab=515, n_layers=1),  # 65 / 129 k-steps
+    dict(d_model=2064, d_ffn=272, n_heads=2, n_kv_heads=1, head_dim=128, vocab=33, n_layers=1),    # wide model, narrow FFN
+])
+def test_gemm_tiling_edge_shapes_bf16(shape):
+    """Model widths that do not divide into the GEMM's tiles evenly (k-steps that are not multiples
+    of the 8 wavefronts or of the split count, output widths that end inside a 32-row band,
+    vocabularies that are not multiples of anything), at 1, 31, 33 and 64 rows."""
+    from paper_2507_18181_amd import binding as B
+    cfg = dict(wl.MODELS["tiny"], **shape)
+    w = wl.make_weights(cfg, 131, "bf16")
+    rng = np.random.default_rng(132)
+    L, cap = 45, 128
+    K, V = wl.seeded_cache(cfg, 133, L, cap, "bf16")
+    om = oracle.OracleModel(cfg, w)
+    ver = _verifier(cfg, w, "bf16", max_nodes=64, capacity=cap)
+    assert B.specasr_uses_mfma(ver.ctx, 8) == 1
+    for n in (1, 31, 33, 64):
+        parents = wl.random_tree(rng, n, max_children=3)
+        tokens = rng.integers(0, cfg["vocab"], n).astype(np.int32)
+        ver.set_cache(K, V, [L])
+        ref = om.tree_forward(np.ascontiguousarray(K[0]), np.ascontiguousarray(V[0]), L, tokens, parents)
+        fw = ver.tree_forward([tokens], [parents])
+        assert fw["status"] == 0
+        check_forward(ref, fw["logits"][0].cpu().numpy(), fw["argmax"][0].cpu().numpy(), TOL_BF16)
+        k1, v1 = ver.get_cache()
+        check_tree_kv(k1[0], v1[0], L, ref, TOL_BF16)
+    ver.close()
