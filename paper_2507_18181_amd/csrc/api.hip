@@ -74,6 +74,8 @@ struct specasr_ctx {
   bool staging_ready = false;
   // second lane for calls that run as several sequence groups: groups alternate between the
   // caller's stream and this one, so one group's latency-bound kernels overlap the other's GEMMs
+  // prefill pipeline: per-layer events, two sets used alternately by consecutive chunks
+  std::vector<hipEvent_t> layer_ev[2];
   hipStream_t lane_stream[kMaxLanes - 1] = {};
   hipEvent_t ev_fork = nullptr, ev_join[kMaxLanes - 1] = {};
 };
@@ -329,8 +331,10 @@ specasr_status upload_meta(specasr_ctx *ctx, const HostStep &hs, char *ws, const
 int ws_lanes(const specasr_ctx *ctx, int batch) {
   if (!ctx->fast) return 1;
   static const int want = [] { const char *e = getenv("SPECASR_LANES"); int v = e ? atoi(e) : kMaxLanes; return v < 1 ? 1 : v > kMaxLanes ? kMaxLanes : v; }();
-  const int groups_max = (int)(((size_t)batch * ctx->cfg.max_nodes + 63) / 64);  // lower bound on groups at full trees
-  return groups_max < want ? (groups_max < 1 ? 1 : groups_max) : want;
+  if (want == 1) return 1;
+  const int groups_max = (int)(((size_t)batch * ctx->cfg.max_nodes + 63) / 64);  // groups at full trees
+  const int n = groups_max < want ? groups_max : want;
+  return n < 2 ? 2 : n;  // two lanes at least: consecutive prefill chunks of one sequence overlap
 }
 
 specasr_status check_ws(const specasr_ctx *ctx, const void *ws, size_t bytes, int batch) {
@@ -459,12 +463,20 @@ void gemm_stage(specasr_ctx *ctx, int stage, bool profiled_layer, const PackedMa
   }
 }
 
+// Ordering between two forwards that run on different streams and meet in the KV cache (chunk c+1
+// of a prefill reads, layer by layer, the rows chunk c writes): `record[l]` is recorded once the
+// K/V rows of layer l are in the cache, `wait[l]` is waited for before layer l's attention.
+struct LayerSync {
+  const hipEvent_t *wait = nullptr;
+  const hipEvent_t *record = nullptr;
+};
+
 // Steps 1-8 with the bf16 MFMA kernels (rows <= 64).  Residual stream, norms, softmax and all
 // accumulators stay fp32; only the MFMA operands (normalised activations, attention output,
 // SwiGLU output) are rounded to bf16.
 void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_kv *kv,
                   const specasr_tree *tree, char *ws, const WsLayout &L, const HostStep &hs,
-                  const ReadOut &ro, hipStream_t st) {
+                  const ReadOut &ro, const LayerSync &sync, hipStream_t st) {
   int32_t *argmax_dev = ro.argmax;
   float *logits_dev = ro.logits;
   const ModelDims &md = ctx->md;
@@ -520,10 +532,14 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
     gemm_stage(ctx, SPECASR_STAGE_QKV, pl, pk.qkv, hb, R, part, pl_qkv, st);
     if (mfma_attn) {
       launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, nrm, ctx->col_k, ctx->col_v, cs, nullptr, qb, qb_lo, kv->k, kv->v, st);
+      if (sync.record) (void)hipEventRecord(sync.record[l], st);
+      if (sync.wait) (void)hipStreamWaitEvent(st, sync.wait[l], 0);
       launch_tree_attention(m, md, g, l, hs.max_total_keys, hs.max_seq_nodes, qb, qb_lo, kv->k, kv->v,
                             (float *)(ws + L.attn_o), (float *)(ws + L.attn_ml), attb, attb_lo, st);
     } else {
       launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, nrm, ctx->col_k, ctx->col_v, cs, q, nullptr, nullptr, kv->k, kv->v, st);
+      if (sync.record) (void)hipEventRecord(sync.record[l], st);
+      if (sync.wait) (void)hipStreamWaitEvent(st, sync.wait[l], 0);
       launch_attention_generic(m, md, g, l, q, kv->k, kv->v, att, st);
       launch_to_bf16(att, R, dq, attb, attb_lo, st);
     }
@@ -548,11 +564,11 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
 
 specasr_status forward_common(specasr_ctx *ctx, specasr_kv *kv, const specasr_tree *tree,
                               const ReadOut &ro, char *ws, const WsLayout &L, const HostStep &hs,
-                              hipStream_t st) {
+                              hipStream_t st, const LayerSync &sync = LayerSync()) {
   KvGeom g{kv->capacity, ctx->md.n_layers, ctx->md.n_kv_heads, ctx->md.head_dim};
   StepMeta m = device_meta(ctx, ws, L, hs.batch, hs);
   if (ctx->fast && m.rows <= 64)
-    forward_fast(ctx, m, g, kv, tree, ws, L, hs, ro, st);
+    forward_fast(ctx, m, g, kv, tree, ws, L, hs, ro, sync, st);
   else
     forward_generic(ctx, m, g, kv, tree, ws, L, ro, st);
   HIP_TRY(ctx, hipGetLastError());
@@ -788,6 +804,8 @@ void specasr_destroy(specasr_ctx *ctx) {
   if (ctx->out_host) (void)hipHostFree(ctx->out_host);
   for (void *p : ctx->owned) (void)hipFree(p);
   if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+  for (auto &set : ctx->layer_ev)
+    for (hipEvent_t e : set) (void)hipEventDestroy(e);
   for (int l = 0; l < kMaxLanes - 1; ++l) {
     if (ctx->ev_join[l]) (void)hipEventDestroy(ctx->ev_join[l]);
     if (ctx->lane_stream[l]) (void)hipStreamDestroy(ctx->lane_stream[l]);
@@ -895,13 +913,32 @@ specasr_status specasr_prefill(specasr_ctx *ctx, specasr_kv *kv, const int32_t *
   const WsLayout L = ws_layout(ctx, B);
   const size_t esz = c.dtype == SPECASR_BF16 ? 2 : 4;
   const size_t seq_kv_bytes = (size_t)c.n_layers * c.n_kv_heads * (size_t)kv->capacity * c.head_dim * esz;
-  int32_t *argmax_dev = reinterpret_cast<int32_t *>(ws + L.outs);  // [max_nodes] of the current chunk
+  int32_t *argmax_dev = reinterpret_cast<int32_t *>(ws + L.outs);  // [batch][max_nodes], last chunk of each sequence
   std::vector<int32_t> chunk_tok(c.max_nodes), chain(c.max_nodes);
   for (int i = 0; i < c.max_nodes; ++i) chain[i] = i - 1;
   std::vector<int32_t> kv_len_now(kv->kv_len, kv->kv_len + B);
-  bool any_result = false;
+  // Consecutive chunks alternate between two lanes.  Chunk c+1 needs, at layer l, the K/V rows chunk
+  // c wrote at layer l and nothing else of it, so it runs one layer behind on the other stream and
+  // its latency-bound kernels fall under the other chunk's GEMMs.
+  size_t n_chunks = 0;
+  for (int b = 0; b < B; ++b) n_chunks += ((size_t)n_pos[b] + c.max_nodes - 1) / c.max_nodes;
+  Lanes lanes{ctx, st, ws, L.total};
+  const bool pipelined = ctx->fast && n_chunks > 1 && ws_lanes(ctx, B) >= 2;
+  if (pipelined) {
+    s = lanes.begin(2, B);
+    if (s != SPECASR_OK) return s;
+    lanes.n = 2;
+    for (auto &set : ctx->layer_ev)
+      while ((int)set.size() < c.n_layers) {
+        hipEvent_t e;
+        HIP_TRY(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        set.push_back(e);
+      }
+  }
+  size_t ci = 0;  // running chunk index over the whole call
   for (int b = 0; b < B; ++b) {
-    for (int c0 = 0; c0 < n_pos[b]; c0 += c.max_nodes) {
+    bool first_of_seq = true;
+    for (int c0 = 0; c0 < n_pos[b]; c0 += c.max_nodes, ++ci) {
       const int32_t n = std::min<int32_t>(c.max_nodes, n_pos[b] - c0);
       const bool last = c0 + n == n_pos[b];
       const size_t at = (size_t)b * max_pos + c0;
@@ -911,28 +948,46 @@ specasr_status specasr_prefill(specasr_ctx *ctx, specasr_kv *kv, const int32_t *
       specasr_tree tv{chunk_tok.data(), chain.data(), &n,
                       input_embeds ? (const char *)input_embeds + at * c.d_model * esz : nullptr,
                       use_embed ? use_embed + at : nullptr};
+      char *wl = pipelined ? lanes.wsp(ci) : ws;
+      hipStream_t sl = pipelined ? lanes.stream(ci) : st;
       HostStep hs;
       build_step(ctx, &tv, 1, kvv.kv_len, &hs);
-      s = upload_meta(ctx, hs, ws, L, st);
+      s = upload_meta(ctx, hs, wl, L, sl);
       if (s != SPECASR_OK) return s;
       ReadOut ro;
-      if (last && next_token) ro.argmax = argmax_dev;
-      s = forward_common(ctx, &kvv, &tv, ro, ws, L, hs, st);
+      if (last && next_token) ro.argmax = argmax_dev + (size_t)b * c.max_nodes;
+      LayerSync sync;
+      if (pipelined) {
+        sync.record = ctx->layer_ev[ci & 1].data();
+        if (!first_of_seq) sync.wait = ctx->layer_ev[(ci + 1) & 1].data();  // the previous chunk's set
+      }
+      s = forward_common(ctx, &kvv, &tv, ro, wl, L, hs, sl, sync);
       if (s != SPECASR_OK) return s;
       kv_len_now[b] += n;  // a chain's rows already sit in slots kv_len .. kv_len+n-1, in order
-      if (last && next_token) {
-        s = ensure_staging(ctx);
-        if (s != SPECASR_OK) return s;
-        HIP_TRY(ctx, hipMemcpyAsync(ctx->out_host + b, argmax_dev + (n - 1), 4, hipMemcpyDeviceToHost, st));
-        any_result = true;
-      }
+      first_of_seq = false;
     }
   }
-  if (any_result) {
-    HIP_TRY(ctx, hipStreamSynchronize(st));
-    for (int b = 0; b < B; ++b) next_token[b] = n_pos[b] > 0 ? ctx->out_host[b] : -1;
-  } else if (next_token) {
-    for (int b = 0; b < B; ++b) next_token[b] = -1;
+  if (pipelined) {
+    s = lanes.end();
+    if (s != SPECASR_OK) return s;
+  }
+  if (next_token) {
+    bool any_result = false;
+    for (int b = 0; b < B; ++b) {
+      next_token[b] = -1;
+      if (n_pos[b] <= 0) continue;
+      const int32_t n_last = (n_pos[b] - 1) % c.max_nodes + 1;
+      s = ensure_staging(ctx);
+      if (s != SPECASR_OK) return s;
+      HIP_TRY(ctx, hipMemcpyAsync(ctx->out_host + b, argmax_dev + (size_t)b * c.max_nodes + (n_last - 1), 4,
+                                  hipMemcpyDeviceToHost, st));
+      any_result = true;
+    }
+    if (any_result) {
+      HIP_TRY(ctx, hipStreamSynchronize(st));
+      for (int b = 0; b < B; ++b)
+        if (n_pos[b] > 0) next_token[b] = ctx->out_host[b];
+    }
   }
   for (int b = 0; b < B; ++b) kv->kv_len[b] = kv_len_now[b];
   return SPECASR_OK;
