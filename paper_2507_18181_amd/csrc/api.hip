@@ -54,6 +54,7 @@ struct specasr_ctx {
   std::vector<void *> owned;  // device allocations made by create
   int col_k = 0, col_v = 0, col_up = 0;  // column offsets inside the concatenated outputs
   size_t part_floats = 0;
+  size_t wide_part_floats = 0;  // partial-sum buffer of a wide prefill pass, in floats (0: no wide path)
   // stage profiling (benchmark aid)
   int prof_stage = -1;
   std::vector<hipEvent_t> prof_ev;  // pairs
@@ -181,6 +182,37 @@ WsLayout ws_layout(const specasr_ctx *ctx, int batch) {
   return L;
 }
 
+// A wide prefill pass takes up to kWideSeqs pieces of max_nodes consecutive positions of ONE
+// sequence at once (each piece is a chain "tree" with its own kv_len on the shared cache), so
+// that the projections become GEMMs over hundreds of rows.  Its buffers follow the lanes'.
+constexpr int kWideSeqs = 8;
+
+WsLayout ws_layout_wide(const specasr_ctx *ctx) {
+  const specasr_config &c = ctx->cfg;
+  WsLayout L{};
+  if (!ctx->fast || ctx->wide_part_floats == 0) return L;
+  const size_t R = (size_t)kWideSeqs * c.max_nodes, Rp = (size_t)wide_row_groups((int)R) * 32;
+  const size_t dq = (size_t)c.n_heads * c.head_dim;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  L.meta_words = meta_words((int)R, kWideSeqs);
+  L.meta = take(L.meta_words * 4);
+  L.rope = take(R * (c.head_dim / 2) * sizeof(float2));
+  L.x = take(R * c.d_model * 4);
+  L.hb = take(2 * Rp * (size_t)c.d_model * 2);
+  L.attb = take(2 * Rp * dq * 2);
+  L.tb = take(2 * Rp * (size_t)c.d_ffn * 2);
+  L.part = take(ctx->wide_part_floats * 4);
+  L.ssq = take(R * (size_t)residual_slabs(c.d_model) * 4);
+  L.qb = take(2 * R * dq * 2);
+  // a pass has >= 2 pieces, so the key chunks of the attention number at most 128 / n_kv_heads + 1
+  const size_t mc = (size_t)128 / c.n_kv_heads + 2;
+  L.attn_o = take(mc * R * dq * 4);
+  L.attn_ml = take(mc * R * c.n_heads * 2 * 4);
+  L.total = off;
+  return L;
+}
+
 // Host-side view of one call: validated and flattened tree metadata.
 struct HostStep {
   int rows = 0, batch = 0;
@@ -289,7 +321,8 @@ specasr_status ensure_staging(specasr_ctx *ctx) {
   if (ctx->staging_ready) return SPECASR_OK;
   const specasr_config &c = ctx->cfg;
   HIP_TRY(ctx, hipGetDevice(&ctx->device));
-  const size_t mw = meta_words(c.max_batch * c.max_nodes, c.max_batch);
+  const int seqs_max = c.max_batch > kWideSeqs ? c.max_batch : kWideSeqs;
+  const size_t mw = meta_words(seqs_max * c.max_nodes, seqs_max);
   for (int i = 0; i < kStagingSlots; ++i) {
     if (!ctx->stage[i].host) HIP_TRY(ctx, hipHostMalloc((void **)&ctx->stage[i].host, mw * 4, hipHostMallocDefault));
     if (!ctx->stage[i].done) HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->stage[i].done, hipEventDisableTiming));
@@ -340,7 +373,7 @@ int ws_lanes(const specasr_ctx *ctx, int batch) {
 specasr_status check_ws(const specasr_ctx *ctx, const void *ws, size_t bytes, int batch) {
   if (!ws) return SPECASR_E_WORKSPACE;
   if (((uintptr_t)ws & 255u) != 0) return SPECASR_E_WORKSPACE;
-  if (bytes < ws_layout(ctx, batch).total * ws_lanes(ctx, batch)) return SPECASR_E_WORKSPACE;
+  if (bytes < ws_layout(ctx, batch).total * ws_lanes(ctx, batch) + ws_layout_wide(ctx).total) return SPECASR_E_WORKSPACE;
   return SPECASR_OK;
 }
 
@@ -454,13 +487,17 @@ specasr_status prof_drain(specasr_ctx *ctx) {
 void gemm_stage(specasr_ctx *ctx, int stage, bool profiled_layer, const PackedMatrix &W,
                 const uint16_t *Xp, int rows, float *part, const GemmPlan &plan, hipStream_t st) {
   const bool prof = ctx->prof_stage == stage && profiled_layer && !ctx->prof_ev.empty();
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;
   if (prof) {
     if (ctx->prof_used + 2 > ctx->prof_ev.size()) (void)prof_drain(ctx);
-    launch_gemm_skinny(W, Xp, rows, part, plan, stage, st, ctx->prof_ev[ctx->prof_used], ctx->prof_ev[ctx->prof_used + 1]);
+    ev0 = ctx->prof_ev[ctx->prof_used];
+    ev1 = ctx->prof_ev[ctx->prof_used + 1];
     ctx->prof_used += 2;
-  } else {
-    launch_gemm_skinny(W, Xp, rows, part, plan, stage, st);
   }
+  if (plan.wide)
+    launch_gemm_wide(W, Xp, rows, part, plan.n_splits, stage, st, ev0, ev1);
+  else
+    launch_gemm_skinny(W, Xp, rows, part, plan, stage, st, ev0, ev1);
 }
 
 // Ordering between two forwards that run on different streams and meet in the KV cache (chunk c+1
@@ -471,7 +508,8 @@ struct LayerSync {
   const hipEvent_t *record = nullptr;
 };
 
-// Steps 1-8 with the bf16 MFMA kernels (rows <= 64).  Residual stream, norms, softmax and all
+// Steps 1-8 with the bf16 MFMA kernels (rows <= 64: skinny GEMMs bound by the weight stream; more
+// rows, a wide prefill pass: tiled GEMMs bound by the matrix cores).  Residual stream, norms, softmax and all
 // accumulators stay fp32; only the MFMA operands (normalised activations, attention output,
 // SwiGLU output) are rounded to bf16.
 void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_kv *kv,
@@ -482,7 +520,8 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
   const ModelDims &md = ctx->md;
   const int d = md.d_model, F = md.d_ffn, V = md.vocab, R = m.rows;
   const int dq = md.n_heads * md.head_dim;
-  const int nb = R <= 32 ? 1 : 2;
+  const bool wide = R > 64;
+  const int nb = R <= 32 ? 1 : R <= 64 ? 2 : wide_row_groups(R);  // row groups of 32 in the packed planes
   float *x = (float *)(ws + L.x), *q = (float *)(ws + L.q), *att = (float *)(ws + L.att);
   float *part = (float *)(ws + L.part), *ssq = (float *)(ws + L.ssq);
   const RowNorm nrm{ssq, residual_slabs(d), d, md.rms_eps};
@@ -498,8 +537,16 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
   GemmPlan pl_gu = plan_gemm(p0.gu.n_bands, p0.gu.ksteps, nb, ctx->n_cu);
   GemmPlan pl_dn = plan_gemm(p0.down.n_bands, p0.down.ksteps, nb, ctx->n_cu);
   GemmPlan pl_lm = plan_gemm(ctx->lm_head.n_bands, ctx->lm_head.ksteps, nb, ctx->n_cu);
+  if (wide) {
+    GemmPlan *pls[5] = {&pl_qkv, &pl_o, &pl_gu, &pl_dn, &pl_lm};
+    const PackedMatrix *pm[5] = {&p0.qkv, &p0.o, &p0.gu, &p0.down, &ctx->lm_head};
+    for (int i = 0; i < 5; ++i) {
+      pls[i]->wide = true;
+      pls[i]->n_splits = wide_gemm_splits(pm[i]->n_bands, pm[i]->ksteps, R, ctx->n_cu);
+    }
+  }
 
-  if (const char *e = getenv("SPECASR_GEMM_SPLITS")) {  // tuning aid: "qkv,o,gate_up,down,lm_head" split counts
+  if (const char *e = wide ? nullptr : getenv("SPECASR_GEMM_SPLITS")) {  // tuning aid: "qkv,o,gate_up,down,lm_head" split counts
     int v[5] = {0, 0, 0, 0, 0};
     sscanf(e, "%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4]);
     GemmPlan *pls[5] = {&pl_qkv, &pl_o, &pl_gu, &pl_dn, &pl_lm};
@@ -517,8 +564,8 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
     const char *nm[5] = {"qkv", "o", "gate_up", "down", "lm_head"};
     const PackedMatrix *pm[5] = {&p0.qkv, &p0.o, &p0.gu, &p0.down, &ctx->lm_head};
     for (int i = 0; i < 5; ++i)
-      fprintf(stderr, "[specasr] %-8s bands=%d ksteps=%d rows=%d: splits=%d ring=%d grid=%d\n", nm[i],
-              pm[i]->n_bands, pm[i]->ksteps, R, pls[i]->n_splits, pls[i]->lw, pls[i]->grid);
+      fprintf(stderr, "[specasr] %-8s bands=%d ksteps=%d rows=%d: %s splits=%d ring=%d grid=%d\n", nm[i],
+              pm[i]->n_bands, pm[i]->ksteps, R, wide ? "wide" : "skinny", pls[i]->n_splits, pls[i]->lw, pls[i]->grid);
   }
   launch_rope_table(m, md.head_dim, md.rope_theta, cs, st);
   launch_embed(m, 1, ctx->w.tok_embed, tree->input_embeds, ctx->cfg.max_nodes, d, x, st);
@@ -528,14 +575,14 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
     const bool pl = l == prof_layer;
     const specasr_layer_weights &lw = ctx->layers[l];
     const PackedLayer &pk = ctx->packed[l];
-    launch_residual_gain(x, part, pending, R, pending_ld, lw.attn_norm, d, hb, hb_lo, ssq, st);
+    launch_residual_gain(x, part, pending, R, pending_ld, lw.attn_norm, d, hb, hb_lo, nb, ssq, st);
     gemm_stage(ctx, SPECASR_STAGE_QKV, pl, pk.qkv, hb, R, part, pl_qkv, st);
     if (mfma_attn) {
       launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, nrm, ctx->col_k, ctx->col_v, cs, nullptr, qb, qb_lo, kv->k, kv->v, st);
       if (sync.record) (void)hipEventRecord(sync.record[l], st);
       if (sync.wait) (void)hipStreamWaitEvent(st, sync.wait[l], 0);
       launch_tree_attention(m, md, g, l, hs.max_total_keys, hs.max_seq_nodes, qb, qb_lo, kv->k, kv->v,
-                            (float *)(ws + L.attn_o), (float *)(ws + L.attn_ml), attb, attb_lo, st);
+                            (float *)(ws + L.attn_o), (float *)(ws + L.attn_ml), attb, attb_lo, nb, st);
     } else {
       launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, nrm, ctx->col_k, ctx->col_v, cs, q, nullptr, nullptr, kv->k, kv->v, st);
       if (sync.record) (void)hipEventRecord(sync.record[l], st);
@@ -544,15 +591,15 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
       launch_to_bf16(att, R, dq, attb, attb_lo, st);
     }
     gemm_stage(ctx, SPECASR_STAGE_O, pl, pk.o, attb, R, part, pl_o, st);
-    launch_residual_gain(x, part, pl_o.n_splits, R, pk.o.ldo, lw.ffn_norm, d, hb, hb_lo, ssq, st);
+    launch_residual_gain(x, part, pl_o.n_splits, R, pk.o.ldo, lw.ffn_norm, d, hb, hb_lo, nb, ssq, st);
     gemm_stage(ctx, SPECASR_STAGE_GATE_UP, pl, pk.gu, hb, R, part, pl_gu, st);
-    launch_swiglu_finish(part, pl_gu.n_splits, R, pk.gu.ldo, nrm, ctx->col_up, F, tb, tb_lo, st);
+    launch_swiglu_finish(part, pl_gu.n_splits, R, pk.gu.ldo, nrm, ctx->col_up, F, tb, tb_lo, nb, st);
     gemm_stage(ctx, SPECASR_STAGE_DOWN, pl, pk.down, tb, R, part, pl_dn, st);
     pending = pl_dn.n_splits;
     pending_ld = pk.down.ldo;
   }
   if (ro.none()) return;
-  launch_residual_gain(x, part, pending, R, pending_ld, ctx->w.final_norm, d, hb, hb_lo, ssq, st);
+  launch_residual_gain(x, part, pending, R, pending_ld, ctx->w.final_norm, d, hb, hb_lo, nb, ssq, st);
   gemm_stage(ctx, SPECASR_STAGE_LM_HEAD, true, ctx->lm_head, hb, R, part, pl_lm, st);
   if (ro.top2)
     launch_top2(m, part, true, pl_lm.n_splits, ctx->lm_head.ldo, nrm, V, ctx->cfg.max_nodes, logits_dev,
@@ -564,10 +611,12 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
 
 specasr_status forward_common(specasr_ctx *ctx, specasr_kv *kv, const specasr_tree *tree,
                               const ReadOut &ro, char *ws, const WsLayout &L, const HostStep &hs,
-                              hipStream_t st, const LayerSync &sync = LayerSync()) {
+                              hipStream_t st, const LayerSync &sync = LayerSync(),
+                              bool wide_pass = false) {
   KvGeom g{kv->capacity, ctx->md.n_layers, ctx->md.n_kv_heads, ctx->md.head_dim};
+  g.shared_cache = wide_pass ? 1 : 0;
   StepMeta m = device_meta(ctx, ws, L, hs.batch, hs);
-  if (ctx->fast && m.rows <= 64)
+  if (ctx->fast && (m.rows <= 64 || wide_pass))
     forward_fast(ctx, m, g, kv, tree, ws, L, hs, ro, sync, st);
   else
     forward_generic(ctx, m, g, kv, tree, ws, L, ro, st);
@@ -672,6 +721,21 @@ specasr_status build_packed(specasr_ctx *ctx) {
       if (need > bound) bound = need;
     }
   ctx->part_floats = bound;
+  // wide prefill passes: 2 .. kWideSeqs pieces of max_nodes rows (MFMA attention only)
+  static const bool wide_off = [] { const char *e = getenv("SPECASR_WIDE"); return e && atoi(e) == 0; }();
+  if (tree_attention_supported(c.head_dim) && !wide_off) {
+    size_t wb = 0;
+    for (int j = 2; j <= kWideSeqs; ++j) {
+      const int rows = j * c.max_nodes;
+      for (const PackedMatrix *pm : mats) {
+        const size_t need = (size_t)wide_gemm_splits(pm->n_bands, pm->ksteps, rows, ctx->n_cu) * pm->ldo * part_rows_pad(rows);
+        if (need > wb) wb = need;
+      }
+    }
+    // a pass of few short pieces (<= 64 rows in all) runs on the skinny kernels in the same buffers
+    if (wb < 64 * bound) wb = 64 * bound;
+    ctx->wide_part_floats = wb;
+  }
   ctx->fast = true;
   return SPECASR_OK;
 }
@@ -816,7 +880,7 @@ void specasr_destroy(specasr_ctx *ctx) {
 
 size_t specasr_workspace_bytes(const specasr_ctx *ctx, int32_t batch) {
   if (!ctx || batch < 1 || batch > ctx->cfg.max_batch) return 0;
-  return ws_layout(ctx, batch).total * ws_lanes(ctx, batch);
+  return ws_layout(ctx, batch).total * ws_lanes(ctx, batch) + ws_layout_wide(ctx).total;
 }
 
 specasr_status specasr_tree_forward(specasr_ctx *ctx, specasr_kv *kv, const specasr_tree *tree,
@@ -917,13 +981,31 @@ specasr_status specasr_prefill(specasr_ctx *ctx, specasr_kv *kv, const int32_t *
   std::vector<int32_t> chunk_tok(c.max_nodes), chain(c.max_nodes);
   for (int i = 0; i < c.max_nodes; ++i) chain[i] = i - 1;
   std::vector<int32_t> kv_len_now(kv->kv_len, kv->kv_len + B);
-  // Consecutive chunks alternate between two lanes.  Chunk c+1 needs, at layer l, the K/V rows chunk
-  // c wrote at layer l and nothing else of it, so it runs one layer behind on the other stream and
-  // its latency-bound kernels fall under the other chunk's GEMMs.
-  size_t n_chunks = 0;
-  for (int b = 0; b < B; ++b) n_chunks += ((size_t)n_pos[b] + c.max_nodes - 1) / c.max_nodes;
+  // Work list.  The part of a sequence in front of its last chunk goes through wide passes of up
+  // to kWideSeqs chunks where the context has them (projections as matrix-core-bound GEMMs over
+  // hundreds of rows); everything else is a chunk of <= max_nodes rows on the skinny kernels.
+  struct Item { int b, c0, n; bool wide; };
+  std::vector<Item> items;
+  const WsLayout LW = ws_layout_wide(ctx);
+  bool any_wide = false;
+  for (int b = 0; b < B; ++b) {
+    int c0 = 0;
+    if (LW.total > 0 && n_pos[b] > 0) {
+      const int n_last = (n_pos[b] - 1) % c.max_nodes + 1, head = n_pos[b] - n_last;
+      while (head - c0 >= 2 * c.max_nodes) {
+        const int n = std::min(head - c0, kWideSeqs * c.max_nodes);
+        items.push_back({b, c0, n, true});
+        any_wide = true;
+        c0 += n;
+      }
+    }
+    for (; c0 < n_pos[b]; c0 += c.max_nodes) items.push_back({b, c0, std::min<int>(c.max_nodes, n_pos[b] - c0), false});
+  }
+  // Without wide passes, consecutive chunks alternate between two lanes.  Chunk c+1 needs, at layer
+  // l, the K/V rows chunk c wrote at layer l and nothing else of it, so it runs one layer behind on
+  // the other stream and its latency-bound kernels fall under the other chunk's GEMMs.
   Lanes lanes{ctx, st, ws, L.total};
-  const bool pipelined = ctx->fast && n_chunks > 1 && ws_lanes(ctx, B) >= 2;
+  const bool pipelined = ctx->fast && !any_wide && items.size() > 1 && ws_lanes(ctx, B) >= 2;
   if (pipelined) {
     s = lanes.begin(2, B);
     if (s != SPECASR_OK) return s;
@@ -935,19 +1017,42 @@ specasr_status specasr_prefill(specasr_ctx *ctx, specasr_kv *kv, const int32_t *
         set.push_back(e);
       }
   }
-  size_t ci = 0;  // running chunk index over the whole call
-  for (int b = 0; b < B; ++b) {
-    bool first_of_seq = true;
-    for (int c0 = 0; c0 < n_pos[b]; c0 += c.max_nodes, ++ci) {
-      const int32_t n = std::min<int32_t>(c.max_nodes, n_pos[b] - c0);
-      const bool last = c0 + n == n_pos[b];
-      const size_t at = (size_t)b * max_pos + c0;
+  char *wide_ws = ws + L.total * ws_lanes(ctx, B);
+  std::vector<int32_t> wide_parents, wide_n, wide_kv;
+  int prev_b = -1;
+  for (size_t ci = 0; ci < items.size(); ++ci) {
+    const Item &it = items[ci];
+    const int b = it.b;
+    const size_t at = (size_t)b * max_pos + it.c0;
+    specasr_kv kvv{(char *)kv->k + (size_t)b * seq_kv_bytes, (char *)kv->v + (size_t)b * seq_kv_bytes,
+                   kv->capacity, 1, &kv_len_now[b]};
+    const void *emb = input_embeds ? (const char *)input_embeds + at * c.d_model * esz : nullptr;
+    if (it.wide) {
+      // piece j: positions c0 + j * max_nodes ..., a chain on top of kv_len + j * max_nodes cached rows
+      const int pieces = it.n / c.max_nodes;
+      wide_parents.resize((size_t)pieces * c.max_nodes);
+      wide_n.assign(pieces, c.max_nodes);
+      wide_kv.resize(pieces);
+      std::vector<int32_t> toks((size_t)it.n, 0);
+      for (int i = 0; i < it.n; ++i) {
+        wide_parents[i] = i % c.max_nodes - 1;
+        if (tokens) toks[i] = tokens[at + i];
+      }
+      for (int j = 0; j < pieces; ++j) wide_kv[j] = kv_len_now[b] + j * c.max_nodes;
+      kvv.batch = pieces;
+      kvv.kv_len = wide_kv.data();
+      specasr_tree tv{toks.data(), wide_parents.data(), wide_n.data(), emb, use_embed ? use_embed + at : nullptr};
+      HostStep hs;
+      build_step(ctx, &tv, pieces, wide_kv.data(), &hs);
+      s = upload_meta(ctx, hs, wide_ws, LW, st);
+      if (s != SPECASR_OK) return s;
+      s = forward_common(ctx, &kvv, &tv, ReadOut(), wide_ws, LW, hs, st, LayerSync(), true);
+      if (s != SPECASR_OK) return s;
+    } else {
+      const int32_t n = it.n;
+      const bool last = it.c0 + n == n_pos[b];
       for (int i = 0; i < n; ++i) chunk_tok[i] = tokens ? tokens[at + i] : 0;
-      specasr_kv kvv{(char *)kv->k + (size_t)b * seq_kv_bytes, (char *)kv->v + (size_t)b * seq_kv_bytes,
-                     kv->capacity, 1, &kv_len_now[b]};
-      specasr_tree tv{chunk_tok.data(), chain.data(), &n,
-                      input_embeds ? (const char *)input_embeds + at * c.d_model * esz : nullptr,
-                      use_embed ? use_embed + at : nullptr};
+      specasr_tree tv{chunk_tok.data(), chain.data(), &n, emb, use_embed ? use_embed + at : nullptr};
       char *wl = pipelined ? lanes.wsp(ci) : ws;
       hipStream_t sl = pipelined ? lanes.stream(ci) : st;
       HostStep hs;
@@ -959,13 +1064,13 @@ specasr_status specasr_prefill(specasr_ctx *ctx, specasr_kv *kv, const int32_t *
       LayerSync sync;
       if (pipelined) {
         sync.record = ctx->layer_ev[ci & 1].data();
-        if (!first_of_seq) sync.wait = ctx->layer_ev[(ci + 1) & 1].data();  // the previous chunk's set
+        if (b == prev_b) sync.wait = ctx->layer_ev[(ci + 1) & 1].data();  // the previous chunk's set
       }
       s = forward_common(ctx, &kvv, &tv, ro, wl, L, hs, sl, sync);
       if (s != SPECASR_OK) return s;
-      kv_len_now[b] += n;  // a chain's rows already sit in slots kv_len .. kv_len+n-1, in order
-      first_of_seq = false;
     }
+    kv_len_now[b] += it.n;  // a chain's rows already sit in slots kv_len .. kv_len+n-1, in order
+    prev_b = b;
   }
   if (pipelined) {
     s = lanes.end();

@@ -45,13 +45,13 @@ __host__ __device__ __forceinline__ int64_t packed_act_offset(int row, int col, 
 }
 
 // Element offset of split-k partial sum (split s, activation row, output column) in the partial-sum
-// buffer: [split][band = col/32][row, padded to rows_pad = 32 or 64][col%32].  One (split, band)
+// buffer: [split][band = col/32][row, padded to rows_pad = 32 or a multiple of 64][col%32].  One (split, band)
 // block is contiguous, so the GEMM writes it with full-line stores and a consumer thread reads
 // 4 consecutive columns as one float4 (col a multiple of 4).
 __host__ __device__ __forceinline__ int64_t part_offset(int s, int row, int col, int n_bands, int rows_pad) {
   return ((((int64_t)s * n_bands + (col >> 5)) * rows_pad + row) << 5) + (col & 31);
 }
-__host__ __device__ __forceinline__ int part_rows_pad(int rows) { return rows <= 32 ? 32 : 64; }
+__host__ __device__ __forceinline__ int part_rows_pad(int rows) { return rows <= 32 ? 32 : (rows + 63) / 64 * 64; }
 
 // ---- per-call tree metadata as the kernels see it ------------------------
 // Rows are the tree nodes of all sequences of the call, flattened without
@@ -83,8 +83,11 @@ struct StepMeta {
 struct KvGeom {
   int64_t capacity;
   int32_t n_layers, n_kv_heads, head_dim;
+  // 1: every sequence of the call is a window onto the cache of sequence 0 (a long chain cut into
+  // pieces that are processed together: piece j is "sequence" j with its own kv_len)
+  int32_t shared_cache = 0;
   __host__ __device__ int64_t row(int32_t seq, int32_t layer, int32_t h, int64_t slot) const {
-    return ((((int64_t)seq * n_layers + layer) * n_kv_heads + h) * capacity + slot) * head_dim;
+    return ((((int64_t)(shared_cache ? 0 : seq) * n_layers + layer) * n_kv_heads + h) * capacity + slot) * head_dim;
   }
 };
 

@@ -329,7 +329,7 @@ template <int HD>
 static void launch_attn_hd(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
                            int max_seq_nodes, int chunk_keys, int n_chunks, bool pair,
                            const uint16_t *qb, const uint16_t *qb_lo, const void *kc, const void *vc,
-                           float *o_part, float *ml_part, uint16_t *out, uint16_t *out_lo,
+                           float *o_part, float *ml_part, uint16_t *out, uint16_t *out_lo, int nb,
                            hipStream_t st) {
   const int G = md.n_heads / md.n_kv_heads;
   const int row_groups = (G * max_seq_nodes + 31) / 32;
@@ -348,7 +348,7 @@ static void launch_attn_hd(const StepMeta &m, const ModelDims &md, const KvGeom 
     tree_attention_kernel<HD, 2><<<grid, 256, lds_bytes(2), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, n_rgb, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, n_chunks, o_part, ml_part);
   }
   dim3 mgrid(md.n_heads, m.rows);
-  tree_attention_merge_kernel<<<mgrid, HD, 0, st>>>(m, md.n_heads, HD, chunk_keys, o_part, ml_part, out, out_lo, m.rows <= 32 ? 1 : 2);
+  tree_attention_merge_kernel<<<mgrid, HD, 0, st>>>(m, md.n_heads, HD, chunk_keys, o_part, ml_part, out, out_lo, nb);
 }
 
 bool tree_attention_supported(int head_dim) { return head_dim == 64 || head_dim == 128; }
@@ -381,7 +381,7 @@ int tree_attention_chunk_keys(int max_total_keys, int n_kv_heads, int batch, int
 void launch_tree_attention(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
                            int max_total_keys, int max_seq_nodes, const uint16_t *qb,
                            const uint16_t *qb_lo, const void *kc, const void *vc, float *o_part,
-                           float *ml_part, uint16_t *out, uint16_t *out_lo, hipStream_t st) {
+                           float *ml_part, uint16_t *out, uint16_t *out_lo, int nb, hipStream_t st) {
   const int G = md.n_heads / md.n_kv_heads;
   const int row_groups = (G * max_seq_nodes + 31) / 32;
   // Two query row groups per workgroup halve the key traffic, but only where their accumulators
@@ -394,9 +394,9 @@ void launch_tree_attention(const StepMeta &m, const ModelDims &md, const KvGeom 
   const int ck = tree_attention_chunk_keys(max_total_keys, md.n_kv_heads, m.batch, n_rgb);
   const int n_chunks = (max_total_keys + ck - 1) / ck;
   if (md.head_dim == 64)
-    launch_attn_hd<64>(m, md, g, layer, max_seq_nodes, ck, n_chunks, pair, qb, qb_lo, kc, vc, o_part, ml_part, out, out_lo, st);
+    launch_attn_hd<64>(m, md, g, layer, max_seq_nodes, ck, n_chunks, pair, qb, qb_lo, kc, vc, o_part, ml_part, out, out_lo, nb, st);
   else
-    launch_attn_hd<128>(m, md, g, layer, max_seq_nodes, ck, n_chunks, pair, qb, qb_lo, kc, vc, o_part, ml_part, out, out_lo, st);
+    launch_attn_hd<128>(m, md, g, layer, max_seq_nodes, ck, n_chunks, pair, qb, qb_lo, kc, vc, o_part, ml_part, out, out_lo, nb, st);
 }
 
 }  // namespace specasr

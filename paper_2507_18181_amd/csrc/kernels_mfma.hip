@@ -245,6 +245,167 @@ hipError_t gemm_skinny_set_lds_limit() {
   return e;
 }
 
+// --------------------------------------------------------------------------- wide GEMM (prefill)
+// The same product for hundreds of activation rows (a prefill pass over many positions at once):
+// now every weight tile is used by all rows, the stage is bound by the matrix cores, and the
+// classical tiling applies.  One workgroup of 4 wavefronts computes 256 output features x 128
+// rows; per stage of 2 k-steps the 16 weight tiles and the 16 activation tiles (hi and lo plane)
+// are copied global -> registers -> LDS as they are (both sides are already in MFMA operand
+// order, so the copy is linear and every LDS access is a conflict-free 16 bytes per lane), double
+// buffered with one barrier per stage.  A wavefront owns 128 features x 64 rows: 4 weight tiles
+// and 2 x 2 activation tiles from LDS feed 16 MFMAs per k-step into 8 accumulator tiles.  Two
+// workgroups fit a compute unit (64 KB LDS, < 256 registers), so one's barrier and LDS phases
+// hide under the other's MFMAs.  Workgroups that share a weight tile (the row tiles of one
+// feature tile) get consecutive slots of one XCD and meet in its L2.
+//   part[s][band][row][o % 32] as for the skinny kernel; nb = row groups of 32 in Xp, a multiple
+//   of 4 (the buffer is allocated to that size; rows >= `rows` hold anything and are not stored).
+// grid.x = 8 * (nb / 4) * ceil(ceil(n_bands / 8) / 8) * S, block 256.
+constexpr int kWideKB = 2;          // k-steps per LDS stage
+constexpr int kWideTileBands = 8;   // 256 output features per workgroup
+constexpr int kWideTileGroups = 4;  // 128 rows per workgroup
+constexpr int kWideStageVecs = (kWideTileBands + 2 * kWideTileGroups) * kWideKB * 64;  // 16-byte vectors per stage
+
+template <int STAGE>
+__global__ __launch_bounds__(256, 2) void gemm_wide_kernel(const u32x4 *__restrict__ Wp,
+                                                           const u32x4 *__restrict__ Xp,
+                                                           float *__restrict__ part, int rows,
+                                                           int rows_pad, int n_bands, int ksteps,
+                                                           int nb, int S) {
+  __shared__ u32x4 lds[2 * kWideStageVecs];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int n_mt = nb / kWideTileGroups, n_nt = (n_bands + kWideTileBands - 1) / kWideTileBands, n_nt8 = (n_nt + 7) / 8;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int mt = slot % n_mt, rest = slot / n_mt;
+  const int nt = (rest % n_nt8) * 8 + xcd, s = rest / n_nt8;
+  if (nt >= n_nt) return;
+  const int k0 = (int)((int64_t)ksteps * s / S), k1 = (int)((int64_t)ksteps * (s + 1) / S);
+  const int wn = wave & 1, wm = wave >> 1;
+  const int64_t x_plane = (int64_t)ksteps * nb * 64;
+
+  // global -> registers: 4 weight tiles and 4 activation tiles per wavefront and stage (tiles past
+  // the matrix edge are clamped to valid ones; their products are never stored or never issued)
+  u32x4 stA[4], stB[4];
+  auto fetch = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int ti = wave * 4 + i;
+      const int band = min(nt * kWideTileBands + (ti >> 1), n_bands - 1), ks = min(kt + (ti & 1), ksteps - 1);
+      stA[i] = load_stream(Wp + ((int64_t)band * ksteps + ks) * 64 + lane);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int ti = wave * 4 + i;
+      const int pl = ti >> 3, ks = min(kt + ((ti >> 2) & 1), ksteps - 1), grp = mt * kWideTileGroups + (ti & 3);
+      stB[i] = Xp[pl * x_plane + ((int64_t)ks * nb + grp) * 64 + lane];
+    }
+  };
+  auto stash = [&](u32x4 *buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) buf[(wave * 4 + i) * 64 + lane] = stA[i];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) buf[(kWideTileBands * kWideKB + wave * 4 + i) * 64 + lane] = stB[i];
+  };
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc[i][g][j] = 0.f;
+  auto compute = [&](const u32x4 *buf, int kt) {
+    const u32x4 *sA = buf, *sB = buf + kWideTileBands * kWideKB * 64;
+#pragma unroll
+    for (int ks = 0; ks < kWideKB; ++ks) {
+      if (kt + ks < k1) {
+        bf16x8 a[4], bh[2], bl[2];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a[i] = __builtin_bit_cast(bf16x8, sA[((4 * wn + i) * kWideKB + ks) * 64 + lane]);
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+          bh[g] = __builtin_bit_cast(bf16x8, sB[((0 * kWideKB + ks) * 4 + 2 * wm + g) * 64 + lane]);
+          bl[g] = __builtin_bit_cast(bf16x8, sB[((1 * kWideKB + ks) * 4 + 2 * wm + g) * 64 + lane]);
+        }
+        // all hi products, then all lo products: 8 independent accumulators between two uses of one
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int g = 0; g < 2; ++g) acc[i][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bh[g], acc[i][g], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int g = 0; g < 2; ++g) acc[i][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bl[g], acc[i][g], 0, 0, 0);
+      }
+    }
+  };
+  fetch(k0);
+  stash(lds);
+  __syncthreads();
+  int cur = 0;
+  for (int kt = k0; kt < k1; kt += kWideKB) {
+    const bool more = kt + kWideKB < k1;
+    if (more) fetch(kt + kWideKB);  // in flight while this stage is multiplied
+    compute(lds + cur * kWideStageVecs, kt);
+    if (more) stash(lds + (cur ^ 1) * kWideStageVecs);  // last read before the previous barrier
+    __syncthreads();
+    cur ^= 1;
+  }
+  // C layout: register j of lane l = row l%32 of the group, output feature 8*(j/4) + 4*(l/32) + j%4
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int band = nt * kWideTileBands + 4 * wn + i;
+    if (band >= n_bands) continue;
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      const int row = (mt * kWideTileGroups + 2 * wm + g) * 32 + (lane & 31);
+      if (row >= rows) continue;
+      float *dst = part + part_offset(s, row, band * 32 + 4 * (lane >> 5), n_bands, rows_pad);
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4 *>(dst + 8 * q) =
+            make_float4(acc[i][g][4 * q], acc[i][g][4 * q + 1], acc[i][g][4 * q + 2], acc[i][g][4 * q + 3]);
+    }
+  }
+}
+
+int wide_row_groups(int rows) { return (rows + 32 * kWideTileGroups - 1) / (32 * kWideTileGroups) * kWideTileGroups; }
+
+// k-split of a wide GEMM: enough workgroups for two per compute unit, as long as a split keeps
+// >= 8 k-steps and the partial sums (written here, read again by the consumer) stay below
+// ~100 MB -- measured on the 7B shapes, beyond that the extra traffic costs more than the
+// fuller machine gains.
+int wide_gemm_splits(int n_bands, int ksteps, int rows, int n_cu) {
+  const int64_t tiles = (int64_t)((n_bands + kWideTileBands - 1) / kWideTileBands) * (wide_row_groups(rows) / kWideTileGroups);
+  int S = 1;
+  while (S < 8 && tiles * S < 2 * n_cu && ksteps / (2 * S) >= 8) S *= 2;
+  const int64_t out_bytes = (int64_t)n_bands * 32 * part_rows_pad(rows) * 4;
+  while (S > 1 && S * out_bytes > (100ll << 20)) S /= 2;
+  return S;
+}
+
+template <int STAGE>
+static void launch_gemm_wide_s(const PackedMatrix &W, const uint16_t *Xp, int rows, float *part,
+                               int n_splits, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  const int nb = wide_row_groups(rows);
+  const int n_nt = (W.n_bands + kWideTileBands - 1) / kWideTileBands;
+  const unsigned grid = 8u * (nb / kWideTileGroups) * ((n_nt + 7) / 8) * n_splits;
+  if (ev0 != nullptr)
+    hipExtLaunchKernelGGL((gemm_wide_kernel<STAGE>), dim3(grid), dim3(256), 0u, st, ev0, ev1, 0u, (const u32x4 *)W.data,
+                          (const u32x4 *)Xp, part, rows, part_rows_pad(rows), W.n_bands, W.ksteps, nb, n_splits);
+  else
+    gemm_wide_kernel<STAGE><<<grid, 256, 0, st>>>((const u32x4 *)W.data, (const u32x4 *)Xp, part, rows, part_rows_pad(rows), W.n_bands, W.ksteps, nb, n_splits);
+}
+
+void launch_gemm_wide(const PackedMatrix &W, const uint16_t *Xp, int rows, float *part, int n_splits,
+                      int stage, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  switch (stage) {
+    case 0: launch_gemm_wide_s<0>(W, Xp, rows, part, n_splits, st, ev0, ev1); break;
+    case 1: launch_gemm_wide_s<1>(W, Xp, rows, part, n_splits, st, ev0, ev1); break;
+    case 2: launch_gemm_wide_s<2>(W, Xp, rows, part, n_splits, st, ev0, ev1); break;
+    case 3: launch_gemm_wide_s<3>(W, Xp, rows, part, n_splits, st, ev0, ev1); break;
+    default: launch_gemm_wide_s<4>(W, Xp, rows, part, n_splits, st, ev0, ev1); break;
+  }
+}
+
 // --------------------------------------------------------------------------- consumers of partial sums
 // RMSNorm is applied in two halves so that no kernel has to see a whole row: this kernel adds the
 // pending partial sums to the residual stream, multiplies by the norm's gain and records the sum
@@ -253,13 +414,13 @@ hipError_t gemm_skinny_set_lds_limit() {
 //   x[r][:]   += sum_s part[s][r][:]            (n_splits may be 0)
 //   hb[r][:]   = hi/lo bf16 planes of x[r][:] * gain[:]
 //   ssq[r][slab] = sum over the slab of x[r][c]^2
-// Block = 8 threads per row (4 columns each), grid = slabs of 32 columns.
+// Block = 8 threads per row (4 columns each, <= 64 rows), grid = (slabs of 32 columns, row blocks).
 constexpr int kSlabCols = 32;
 __global__ __launch_bounds__(512) void residual_gain_kernel(float *x, const float *part, int n_splits,
                                                             int rows, int ldp, const uint16_t *gain,
                                                             int d, uint16_t *hb, uint16_t *hb_lo,
                                                             int nb, float *ssq, int n_slab) {
-  const int r = threadIdx.x >> 3, c = blockIdx.x * kSlabCols + (threadIdx.x & 7) * 4;
+  const int r = blockIdx.y * 64 + (threadIdx.x >> 3), c = blockIdx.x * kSlabCols + (threadIdx.x & 7) * 4;
   const bool ok = r < rows && c < d;
   float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
   if (ok) {
@@ -308,10 +469,12 @@ __global__ __launch_bounds__(512) void residual_gain_kernel(float *x, const floa
 int residual_slabs(int d) { return (d + kSlabCols - 1) / kSlabCols; }
 
 void launch_residual_gain(float *x, const float *part, int n_splits, int rows, int ldp,
-                          const void *gain, int d, uint16_t *hb, uint16_t *hb_lo, float *ssq,
+                          const void *gain, int d, uint16_t *hb, uint16_t *hb_lo, int nb, float *ssq,
                           hipStream_t st) {
   const int n_slab = residual_slabs(d);
-  residual_gain_kernel<<<n_slab, ((rows + 7) / 8) * 64, 0, st>>>(x, part, n_splits, rows, ldp, (const uint16_t *)gain, d, hb, hb_lo, rows <= 32 ? 1 : 2, ssq, n_slab);
+  const int per_block = rows < 64 ? rows : 64;
+  dim3 grid(n_slab, (rows + 63) / 64);
+  residual_gain_kernel<<<grid, ((per_block + 7) / 8) * 64, 0, st>>>(x, part, n_splits, rows, ldp, (const uint16_t *)gain, d, hb, hb_lo, nb, ssq, n_slab);
 }
 
 // q, k, v = sum of partials; rotary embedding at the node's depth position (Sec. II-B: each
@@ -410,9 +573,9 @@ __global__ __launch_bounds__(256) void swiglu_finish_kernel(const float *part, i
 }
 
 void launch_swiglu_finish(const float *part, int n_splits, int rows, int ldp, const RowNorm &nrm,
-                          int col_up, int F, uint16_t *t, uint16_t *t_lo, hipStream_t st) {
+                          int col_up, int F, uint16_t *t, uint16_t *t_lo, int nb, hipStream_t st) {
   dim3 grid((F / 4 + 255) / 256, rows);
-  swiglu_finish_kernel<<<grid, 256, 0, st>>>(part, n_splits, rows, ldp, nrm, col_up, F, t, t_lo, rows <= 32 ? 1 : 2);
+  swiglu_finish_kernel<<<grid, 256, 0, st>>>(part, n_splits, rows, ldp, nrm, col_up, F, t, t_lo, nb);
 }
 
 // fp32 -> bf16 row conversion (attention output feeding the output projection)

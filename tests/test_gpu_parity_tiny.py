@@ -455,13 +455,32 @@ def test_prefill_entry_point_equals_oracle_prefill(dtype, tol, max_nodes):
     that are not multiples of the chunk size; one sequence that already holds a prefix; one with
     nothing to add): cache rows, kv_len and the greedy token after the last position equal the
     oracle's prefill of each sequence alone."""
+    _check_prefill(dtype, tol, max_nodes, n_audio=[70, 0, 33], n_text=[41, 0, 9], L0=[0, 12, 20],
+                   cap=192, max_pos=120)
+
+
+@pytest.mark.parametrize("max_nodes,n_audio,n_text", [
+    (16, [250, 100, 64], [63, 15, 16]),     # 19 pieces + 9: passes of 128, 128, 48 rows; 7 pieces (112 rows); 4 pieces (64 rows)
+    (64, [150, 0, 140], [52, 0, 10]),       # 3 pieces (192 rows, half a row tile empty); nothing; 2 pieces (128 rows)
+    (24, [300, 20, 0], [0, 0, 49]),         # 12 pieces: 192 + 96 rows, embeddings only; one chunk; tokens only
+])
+def test_prefill_wide_passes_equal_oracle_prefill(max_nodes, n_audio, n_text):
+    """Long prefixes: the library takes everything in front of the last chunk of a sequence in
+    passes of up to 8 chunks at once, whose projections run on the tiled (matrix-core-bound) GEMM
+    -- row counts that fill, half fill and overflow its 128-row tiles, feature counts that leave a
+    partial 256-feature tile (gate|up has 44 bands) and an odd number of k-steps (down: 43).  The
+    result is the same as the oracle's position-by-chunk prefill."""
+    _check_prefill("bf16", TOL_BF16, max_nodes, n_audio=n_audio, n_text=n_text, L0=[7, 0, 20],
+                   cap=400, max_pos=320)
+
+
+def _check_prefill(dtype, tol, max_nodes, n_audio, n_text, L0, cap, max_pos):
     cfg = wl.MODELS["tiny"]
     w = wl.make_weights(cfg, 97, dtype)
     rng = np.random.default_rng(98)
-    cap, d = 192, cfg["d_model"]
+    d = cfg["d_model"]
     om = oracle.OracleModel(cfg, w)
-    n_audio, n_text, L0 = [70, 0, 33], [41, 0, 9], [0, 12, 20]
-    nb, max_pos = 3, 120
+    nb = 3
     ver = _verifier(cfg, w, dtype, max_nodes=max_nodes, capacity=cap, max_batch=nb)
     K, V = wl.seeded_cache(cfg, 99, np.asarray(L0, np.int32), cap, dtype, batch=nb)
     ver.set_cache(K, V, L0)
@@ -501,7 +520,7 @@ def test_prefill_entry_point_equals_oracle_prefill(dtype, tol, max_nodes):
             assert out["next_token"][b] == int(np.argmax(last))
     # error paths enqueue nothing: overflow and a bad token id leave kv_len alone
     before = ver.kv_len.copy()
-    assert ver.prefill([[1] * 200, [], []])["status"] == -4
+    assert ver.prefill([[1] * (cap + 8), [], []])["status"] == -4
     assert ver.prefill([[cfg["vocab"]], [], []])["status"] == -3
     assert np.array_equal(ver.kv_len, before)
     ver.close()
