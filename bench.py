@@ -22,6 +22,7 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 
@@ -83,7 +84,8 @@ def bench_prefill(args, spec, cfg, w_host, ver, stage_id, t_gen, log):
     log("prefill warm-up")
     for _ in range(warm):
         step()
-    assert B.specasr_profile_stage(ver.ctx, stage_id, True) == 0
+    wide = B.specasr_uses_mfma(ver.ctx, 64) == 1 and T > 3 * 64
+    assert B.specasr_profile_stage(ver.ctx, stage_id, 2 if wide else 1) == 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
@@ -91,21 +93,36 @@ def bench_prefill(args, spec, cfg, w_host, ver, stage_id, t_gen, log):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     rc, stage_ms, stage_launches, stage_bytes = B.specasr_stage_time(ver.ctx)
+    rc2, stage_rows = B.specasr_stage_rows(ver.ctx)
     B.specasr_profile_stage(ver.ctx, stage_id, False)
     kern_ms = stage_ms / max(1, stage_launches)
-    kern_gbs = stage_bytes / (kern_ms * 1e-3) / 1e9
+    if wide and stage_launches > 0:
+        # the tiled GEMM of the wide passes: algorithmic flops = 2 x rows x weight elements (the
+        # kernel issues twice that on the matrix cores: hi and lo activation plane)
+        rows_avg = stage_rows / stage_launches
+        flops = 2.0 * rows_avg * (stage_bytes / 2.0)
+        tf = flops / (kern_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "gemm_wide_kernel (%s projection, %.0f rows per launch)" % (args.stage, rows_avg),
+                    "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                    "launches_timed": stage_launches, "avg_launch_us": round(kern_ms * 1e3, 2),
+                    "flops_per_launch": flops, "mfma_flops_issued_per_launch": 2.0 * flops}
+    else:
+        kern_gbs = stage_bytes / (kern_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "gemm_skinny_kernel (%s projection, 64 rows)" % args.stage,
+                    "achieved": round(kern_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(kern_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                    "launches_timed": stage_launches, "avg_launch_us": round(kern_ms * 1e3, 2),
+                    "bytes_per_launch": stage_bytes}
     result = {
         "metric": "prefill_positions_per_s", "value": round(T * steps / dt, 1), "unit": "positions/s",
         "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": round(dt / steps * 1e3, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": args.workload + " (prefix prefill)", "model": spec["model"],
-                   "audio_positions": n_a, "prompt_tokens": n_t, "chunk": 64, "batch": 1},
-        "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel (%s projection, 64 rows)" % args.stage,
-                     "achieved": round(kern_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(kern_gbs / HBM_PEAK_GBS, 4), "traffic": None,
-                     "launches_timed": stage_launches, "avg_launch_us": round(kern_ms * 1e3, 2),
-                     "bytes_per_launch": stage_bytes},
+                   "audio_positions": n_a, "prompt_tokens": n_t, "chunk": 64,
+                   "wide_pass_rows": 512 if wide else 0, "batch": 1},
+        "roofline": roofline,
         "weights_gen_s": round(t_gen, 1),
     }
     if not args.no_cpu_baseline:

@@ -32,7 +32,8 @@ EXPORTS = ("specasr_create", "specasr_destroy", "specasr_workspace_bytes", "spec
            "specasr_tree_forward", "specasr_tree_forward_top2", "specasr_prefill", "specasr_accept",
            "specasr_accept_from_logits",
            "specasr_commit", "specasr_strerror", "specasr_last_hip_error", "specasr_abi_version",
-           "specasr_uses_mfma", "specasr_profile_stage", "specasr_stage_time")
+           "specasr_uses_mfma", "specasr_profile_stage", "specasr_stage_time",
+           "specasr_stage_rows")
 SPECASR_STAGE_QKV, SPECASR_STAGE_O, SPECASR_STAGE_GATE_UP, SPECASR_STAGE_DOWN, SPECASR_STAGE_LM_HEAD = range(5)
 
 
@@ -124,6 +125,8 @@ def load_library(path=None):
     lib.specasr_stage_time.restype = C.c_int
     lib.specasr_stage_time.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64),
                                        C.POINTER(C.c_double)]
+    lib.specasr_stage_rows.restype = C.c_int
+    lib.specasr_stage_rows.argtypes = [vp, C.POINTER(C.c_int64)]
     if path is None:
         _lib = lib
     return lib
@@ -196,7 +199,15 @@ def specasr_uses_mfma(ctx, rows):
 
 
 def specasr_profile_stage(ctx, stage, enable):
-    return load_library().specasr_profile_stage(ctx, stage, 1 if enable else 0)
+    """enable: False/0 off, True/1 every launch of the stage, 2 only the wide (prefill) kernel."""
+    return load_library().specasr_profile_stage(ctx, stage, int(enable))
+
+
+def specasr_stage_rows(ctx):
+    """-> (status, activation rows summed over the timed launches)."""
+    n = C.c_int64(0)
+    rc = load_library().specasr_stage_rows(ctx, C.byref(n))
+    return rc, n.value
 
 
 def specasr_stage_time(ctx):

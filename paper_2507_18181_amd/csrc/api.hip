@@ -57,6 +57,8 @@ struct specasr_ctx {
   size_t wide_part_floats = 0;  // partial-sum buffer of a wide prefill pass, in floats (0: no wide path)
   // stage profiling (benchmark aid)
   int prof_stage = -1;
+  int prof_mode = 1;         // 1: every launch of the stage, 2: only launches of the wide (prefill) kernel
+  int64_t prof_rows = 0;     // activation rows summed over the timed launches
   std::vector<hipEvent_t> prof_ev;  // pairs
   size_t prof_used = 0;             // events recorded and not yet accumulated
   double prof_ms = 0.0;
@@ -486,13 +488,14 @@ specasr_status prof_drain(specasr_ctx *ctx) {
 // Launches one projection GEMM; brackets it with events when it is the profiled one.
 void gemm_stage(specasr_ctx *ctx, int stage, bool profiled_layer, const PackedMatrix &W,
                 const uint16_t *Xp, int rows, float *part, const GemmPlan &plan, hipStream_t st) {
-  const bool prof = ctx->prof_stage == stage && profiled_layer && !ctx->prof_ev.empty();
+  const bool prof = ctx->prof_stage == stage && profiled_layer && !ctx->prof_ev.empty() && (ctx->prof_mode != 2 || plan.wide);
   hipEvent_t ev0 = nullptr, ev1 = nullptr;
   if (prof) {
     if (ctx->prof_used + 2 > ctx->prof_ev.size()) (void)prof_drain(ctx);
     ev0 = ctx->prof_ev[ctx->prof_used];
     ev1 = ctx->prof_ev[ctx->prof_used + 1];
     ctx->prof_used += 2;
+    ctx->prof_rows += rows;
   }
   if (plan.wide)
     launch_gemm_wide(W, Xp, rows, part, plan.n_splits, stage, st, ev0, ev1);
@@ -784,9 +787,11 @@ specasr_status specasr_profile_stage(specasr_ctx *ctx, int32_t stage, int32_t en
       ctx->prof_ev.push_back(e);
     }
     ctx->prof_stage = stage;
+    ctx->prof_mode = enable == 2 ? 2 : 1;
     ctx->prof_used = 0;
     ctx->prof_ms = 0.0;
     ctx->prof_launches = 0;
+    ctx->prof_rows = 0;
   } else {
     ctx->prof_stage = -1;
   }
@@ -805,6 +810,15 @@ specasr_status specasr_stage_time(specasr_ctx *ctx, double *total_ms, int64_t *l
   *total_ms = ctx->prof_ms;
   *launches = ctx->prof_launches;
   *weight_bytes_per_launch = elems[ctx->prof_stage] * 2.0;
+  return SPECASR_OK;
+}
+
+specasr_status specasr_stage_rows(specasr_ctx *ctx, int64_t *rows) {
+  if (!ctx || !rows) return SPECASR_E_NULL;
+  if (ctx->prof_stage < 0 || !ctx->fast) return SPECASR_E_UNSUPPORTED;
+  specasr_status s = prof_drain(ctx);
+  if (s != SPECASR_OK) return s;
+  *rows = ctx->prof_rows;
   return SPECASR_OK;
 }
 
