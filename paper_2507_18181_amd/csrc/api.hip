@@ -189,15 +189,17 @@ WsLayout ws_layout(const specasr_ctx *ctx, int batch) {
 // that the projections become GEMMs over hundreds of rows.  Its buffers follow the lanes'.
 constexpr int kWideSeqs = 8;
 
-WsLayout ws_layout_wide(const specasr_ctx *ctx) {
+inline int wide_seqs(int batch) { return batch > kWideSeqs ? batch : kWideSeqs; }
+
+WsLayout ws_layout_wide(const specasr_ctx *ctx, int batch) {
   const specasr_config &c = ctx->cfg;
   WsLayout L{};
   if (!ctx->fast || ctx->wide_part_floats == 0) return L;
-  const size_t R = (size_t)kWideSeqs * c.max_nodes, Rp = (size_t)wide_row_groups((int)R) * 32;
+  const size_t R = (size_t)wide_seqs(batch) * c.max_nodes, Rp = (size_t)wide_row_groups((int)R) * 32;
   const size_t dq = (size_t)c.n_heads * c.head_dim;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-  L.meta_words = meta_words((int)R, kWideSeqs);
+  L.meta_words = meta_words((int)R, wide_seqs(batch));
   L.meta = take(L.meta_words * 4);
   L.rope = take(R * (c.head_dim / 2) * sizeof(float2));
   L.x = take(R * c.d_model * 4);
@@ -211,6 +213,12 @@ WsLayout ws_layout_wide(const specasr_ctx *ctx) {
   const size_t mc = (size_t)128 / c.n_kv_heads + 2;
   L.attn_o = take(mc * R * dq * 4);
   L.attn_ml = take(mc * R * c.n_heads * 2 * 4);
+  // read-out of a wide verify / draft forward (a prefill pass has none)
+  const size_t nblk = (size_t)logits_argmax_blocks(c.vocab);
+  L.blk_val = take(R * nblk * 4);
+  L.blk_idx = take(R * nblk * 4);
+  L.top2_v = take(R * (size_t)top2_blocks(c.vocab) * 3 * 4);
+  L.top2_i = take(R * (size_t)top2_blocks(c.vocab) * 2 * 4);
   L.total = off;
   return L;
 }
@@ -375,7 +383,7 @@ int ws_lanes(const specasr_ctx *ctx, int batch) {
 specasr_status check_ws(const specasr_ctx *ctx, const void *ws, size_t bytes, int batch) {
   if (!ws) return SPECASR_E_WORKSPACE;
   if (((uintptr_t)ws & 255u) != 0) return SPECASR_E_WORKSPACE;
-  if (bytes < ws_layout(ctx, batch).total * ws_lanes(ctx, batch) + ws_layout_wide(ctx).total) return SPECASR_E_WORKSPACE;
+  if (bytes < ws_layout(ctx, batch).total * ws_lanes(ctx, batch) + ws_layout_wide(ctx, batch).total) return SPECASR_E_WORKSPACE;
   return SPECASR_OK;
 }
 
@@ -545,7 +553,9 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
     const PackedMatrix *pm[5] = {&p0.qkv, &p0.o, &p0.gu, &p0.down, &ctx->lm_head};
     for (int i = 0; i < 5; ++i) {
       pls[i]->wide = true;
-      pls[i]->n_splits = wide_gemm_splits(pm[i]->n_bands, pm[i]->ksteps, R, ctx->n_cu);
+      int S = wide_gemm_splits(pm[i]->n_bands, pm[i]->ksteps, R, ctx->n_cu);
+      while (S > 1 && (size_t)S * pm[i]->ldo * part_rows_pad(R) > ctx->wide_part_floats) S /= 2;
+      pls[i]->n_splits = S;
     }
   }
 
@@ -615,11 +625,11 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
 specasr_status forward_common(specasr_ctx *ctx, specasr_kv *kv, const specasr_tree *tree,
                               const ReadOut &ro, char *ws, const WsLayout &L, const HostStep &hs,
                               hipStream_t st, const LayerSync &sync = LayerSync(),
-                              bool wide_pass = false) {
+                              bool wide_ws = false, bool shared_cache = false) {
   KvGeom g{kv->capacity, ctx->md.n_layers, ctx->md.n_kv_heads, ctx->md.head_dim};
-  g.shared_cache = wide_pass ? 1 : 0;
+  g.shared_cache = shared_cache ? 1 : 0;
   StepMeta m = device_meta(ctx, ws, L, hs.batch, hs);
-  if (ctx->fast && (m.rows <= 64 || wide_pass))
+  if (ctx->fast && (m.rows <= 64 || wide_ws))
     forward_fast(ctx, m, g, kv, tree, ws, L, hs, ro, sync, st);
   else
     forward_generic(ctx, m, g, kv, tree, ws, L, ro, st);
@@ -638,15 +648,26 @@ struct SeqGroup {
 // The MFMA kernels take at most 64 activation rows, so a call with more tree nodes in total is
 // run as consecutive groups of whole sequences with <= 64 rows each (a tree has <= 64 nodes);
 // the dtype-generic kernels take the whole call at once.
-std::vector<SeqGroup> split_call(const specasr_ctx *ctx, const specasr_kv *kv, const specasr_tree *tree) {
+// From kWideMinRows rows on (tuning aid: SPECASR_WIDE_MIN_ROWS) the whole call is ONE group on the
+// wide kernels instead: the weights are streamed once, not once per group.
+int wide_min_rows() {
+  static const int v = [] { const char *e = getenv("SPECASR_WIDE_MIN_ROWS"); const int x = e ? atoi(e) : 129; return x < 65 ? 65 : x; }();
+  return v;
+}
+
+std::vector<SeqGroup> split_call(const specasr_ctx *ctx, const specasr_kv *kv, const specasr_tree *tree,
+                                 bool *wide) {
   const specasr_config &c = ctx->cfg;
+  int total = 0;
+  for (int b = 0; b < kv->batch; ++b) total += tree->n_nodes[b];
+  *wide = ctx->fast && ctx->wide_part_floats > 0 && total >= wide_min_rows();
   const size_t esz = c.dtype == SPECASR_BF16 ? 2 : 4;
   const size_t seq_kv_bytes = (size_t)c.n_layers * c.n_kv_heads * (size_t)kv->capacity * c.head_dim * esz;
   std::vector<SeqGroup> out;
   int b = 0;
   while (b < kv->batch) {
     int e = b, rows = 0;
-    while (e < kv->batch && (!ctx->fast || rows + tree->n_nodes[e] <= 64)) rows += tree->n_nodes[e++];
+    while (e < kv->batch && (!ctx->fast || *wide || rows + tree->n_nodes[e] <= 64)) rows += tree->n_nodes[e++];
     SeqGroup g;
     g.s0 = b;
     g.kv.k = (char *)kv->k + (size_t)b * seq_kv_bytes;
@@ -724,12 +745,12 @@ specasr_status build_packed(specasr_ctx *ctx) {
       if (need > bound) bound = need;
     }
   ctx->part_floats = bound;
-  // wide prefill passes: 2 .. kWideSeqs pieces of max_nodes rows (MFMA attention only)
+  // wide passes: more than 64 rows at once -- prefill pieces or the trees of a batch (MFMA attention only)
   static const bool wide_off = [] { const char *e = getenv("SPECASR_WIDE"); return e && atoi(e) == 0; }();
   if (tree_attention_supported(c.head_dim) && !wide_off) {
     size_t wb = 0;
-    for (int j = 2; j <= kWideSeqs; ++j) {
-      const int rows = j * c.max_nodes;
+    const int rows_max = wide_seqs(c.max_batch) * c.max_nodes;
+    for (int rows = 64; rows < rows_max + 64; rows += 64) {  // splits and padding change only at multiples of 64
       for (const PackedMatrix *pm : mats) {
         const size_t need = (size_t)wide_gemm_splits(pm->n_bands, pm->ksteps, rows, ctx->n_cu) * pm->ldo * part_rows_pad(rows);
         if (need > wb) wb = need;
@@ -894,7 +915,7 @@ void specasr_destroy(specasr_ctx *ctx) {
 
 size_t specasr_workspace_bytes(const specasr_ctx *ctx, int32_t batch) {
   if (!ctx || batch < 1 || batch > ctx->cfg.max_batch) return 0;
-  return ws_layout(ctx, batch).total * ws_lanes(ctx, batch) + ws_layout_wide(ctx).total;
+  return ws_layout(ctx, batch).total * ws_lanes(ctx, batch) + ws_layout_wide(ctx, batch).total;
 }
 
 specasr_status specasr_tree_forward(specasr_ctx *ctx, specasr_kv *kv, const specasr_tree *tree,
@@ -911,20 +932,24 @@ specasr_status specasr_tree_forward(specasr_ctx *ctx, specasr_kv *kv, const spec
   char *ws = (char *)workspace;
   const WsLayout L = ws_layout(ctx, kv->batch);
   const size_t MN = (size_t)ctx->cfg.max_nodes;
-  std::vector<SeqGroup> groups = split_call(ctx, kv, tree);
+  bool wide = false;
+  std::vector<SeqGroup> groups = split_call(ctx, kv, tree, &wide);
+  const WsLayout Lg = wide ? ws_layout_wide(ctx, kv->batch) : L;  // a wide call is one group in the wide buffers
+  char *wide_ws = ws + L.total * ws_lanes(ctx, kv->batch);
   Lanes lanes{ctx, st, ws, L.total};
   s = lanes.begin(groups.size(), kv->batch);
   if (s != SPECASR_OK) return s;
   for (size_t gi = 0; gi < groups.size(); ++gi) {
     SeqGroup &grp = groups[gi];
+    char *wl = wide ? wide_ws : lanes.wsp(gi);
     HostStep hs;
     build_step(ctx, &grp.tree, grp.kv.batch, grp.kv.kv_len, &hs);
-    s = upload_meta(ctx, hs, lanes.wsp(gi), L, lanes.stream(gi));
+    s = upload_meta(ctx, hs, wl, Lg, lanes.stream(gi));
     if (s != SPECASR_OK) return s;
     ReadOut ro;
     ro.argmax = argmax_dev + grp.s0 * MN;
     ro.logits = logits_dev ? logits_dev + grp.s0 * MN * ctx->cfg.vocab : nullptr;
-    s = forward_common(ctx, &grp.kv, &grp.tree, ro, lanes.wsp(gi), L, hs, lanes.stream(gi));
+    s = forward_common(ctx, &grp.kv, &grp.tree, ro, wl, Lg, hs, lanes.stream(gi), LayerSync(), wide);
     if (s != SPECASR_OK) return s;
   }
   return lanes.end();
@@ -944,21 +969,25 @@ specasr_status specasr_tree_forward_top2(specasr_ctx *ctx, specasr_kv *kv, const
   char *ws = (char *)workspace;
   const WsLayout L = ws_layout(ctx, kv->batch);
   const size_t MN = (size_t)ctx->cfg.max_nodes;
-  std::vector<SeqGroup> groups = split_call(ctx, kv, tree);
+  bool wide = false;
+  std::vector<SeqGroup> groups = split_call(ctx, kv, tree, &wide);
+  const WsLayout Lg = wide ? ws_layout_wide(ctx, kv->batch) : L;  // a wide call is one group in the wide buffers
+  char *wide_ws = ws + L.total * ws_lanes(ctx, kv->batch);
   Lanes lanes{ctx, st, ws, L.total};
   s = lanes.begin(groups.size(), kv->batch);
   if (s != SPECASR_OK) return s;
   for (size_t gi = 0; gi < groups.size(); ++gi) {
     SeqGroup &grp = groups[gi];
+    char *wl = wide ? wide_ws : lanes.wsp(gi);
     HostStep hs;
     build_step(ctx, &grp.tree, grp.kv.batch, grp.kv.kv_len, &hs);
-    s = upload_meta(ctx, hs, lanes.wsp(gi), L, lanes.stream(gi));
+    s = upload_meta(ctx, hs, wl, Lg, lanes.stream(gi));
     if (s != SPECASR_OK) return s;
     ReadOut ro;
     ro.top2 = top2_dev + grp.s0 * MN * 2;
     ro.prob = top1_prob_dev + grp.s0 * MN;
     ro.logits = logits_dev ? logits_dev + grp.s0 * MN * ctx->cfg.vocab : nullptr;
-    s = forward_common(ctx, &grp.kv, &grp.tree, ro, lanes.wsp(gi), L, hs, lanes.stream(gi));
+    s = forward_common(ctx, &grp.kv, &grp.tree, ro, wl, Lg, hs, lanes.stream(gi), LayerSync(), wide);
     if (s != SPECASR_OK) return s;
   }
   return lanes.end();
@@ -1000,7 +1029,7 @@ specasr_status specasr_prefill(specasr_ctx *ctx, specasr_kv *kv, const int32_t *
   // hundreds of rows); everything else is a chunk of <= max_nodes rows on the skinny kernels.
   struct Item { int b, c0, n; bool wide; };
   std::vector<Item> items;
-  const WsLayout LW = ws_layout_wide(ctx);
+  const WsLayout LW = ws_layout_wide(ctx, B);
   bool any_wide = false;
   for (int b = 0; b < B; ++b) {
     int c0 = 0;
@@ -1060,7 +1089,7 @@ specasr_status specasr_prefill(specasr_ctx *ctx, specasr_kv *kv, const int32_t *
       build_step(ctx, &tv, pieces, wide_kv.data(), &hs);
       s = upload_meta(ctx, hs, wide_ws, LW, st);
       if (s != SPECASR_OK) return s;
-      s = forward_common(ctx, &kvv, &tv, ReadOut(), wide_ws, LW, hs, st, LayerSync(), true);
+      s = forward_common(ctx, &kvv, &tv, ReadOut(), wide_ws, LW, hs, st, LayerSync(), true, true);
       if (s != SPECASR_OK) return s;
     } else {
       const int32_t n = it.n;
@@ -1228,24 +1257,26 @@ specasr_status specasr_verify_tree(specasr_ctx *ctx, specasr_kv *kv, const speca
   int32_t *o = reinterpret_cast<int32_t *>(ws + L.outs);
   const size_t BN = (size_t)B * c.max_nodes, MN = (size_t)c.max_nodes;
   int32_t *argmax_dev = o, *path_dev = o + BN, *len_dev = o + 2 * BN, *next_dev = len_dev + B;
-  std::vector<SeqGroup> groups = split_call(ctx, kv, tree);
+  bool wide = false;
+  std::vector<SeqGroup> groups = split_call(ctx, kv, tree, &wide);
+  const WsLayout Lg = wide ? ws_layout_wide(ctx, B) : L;  // a wide call is one group in the wide buffers
   Lanes lanes{ctx, st, ws, L.total};
   s = lanes.begin(groups.size(), B);
   if (s != SPECASR_OK) return s;
   for (size_t gi = 0; gi < groups.size(); ++gi) {
     SeqGroup &grp = groups[gi];
-    char *wl = lanes.wsp(gi);
+    char *wl = wide ? ws + L.total * ws_lanes(ctx, B) : lanes.wsp(gi);
     hipStream_t sl = lanes.stream(gi);
     HostStep hs;
     build_step(ctx, &grp.tree, grp.kv.batch, grp.kv.kv_len, &hs);
-    s = upload_meta(ctx, hs, wl, L, sl);
+    s = upload_meta(ctx, hs, wl, Lg, sl);
     if (s != SPECASR_OK) return s;
     ReadOut ro;
     ro.argmax = argmax_dev + grp.s0 * MN;
     ro.logits = out->logits ? out->logits + grp.s0 * MN * c.vocab : nullptr;
-    s = forward_common(ctx, &grp.kv, &grp.tree, ro, wl, L, hs, sl);
+    s = forward_common(ctx, &grp.kv, &grp.tree, ro, wl, Lg, hs, sl, LayerSync(), wide);
     if (s != SPECASR_OK) return s;
-    StepMeta m = device_meta(ctx, wl, L, grp.kv.batch, hs);
+    StepMeta m = device_meta(ctx, wl, Lg, grp.kv.batch, hs);
     KvGeom g{kv->capacity, c.n_layers, c.n_kv_heads, c.head_dim};
     launch_accept(m, c.max_nodes, argmax_dev + grp.s0 * MN, path_dev + grp.s0 * MN, len_dev + grp.s0, next_dev + grp.s0, sl);
     launch_compact(c.dtype, g, grp.kv.batch, c.max_nodes, m.kv_len, path_dev + grp.s0 * MN, len_dev + grp.s0, grp.kv.k, grp.kv.v, sl);

@@ -31,6 +31,19 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
 }
 
+// Two finite floats -> their hi planes packed (a in the low half) and their lo planes packed, with
+// the hardware's round-to-nearest-even conversion (one v_cvt_pk_bf16_f32 per pair and plane; the
+// same values as split_bf16 for the probabilities this is used on).
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+__device__ __forceinline__ void split_bf16_pair(float a, float b, uint32_t &hi, uint32_t &lo) {
+  const bf16x2 h = __builtin_convertvector((f32x2){a, b}, bf16x2);
+  hi = __builtin_bit_cast(uint32_t, h);
+  const float ra = a - __uint_as_float(hi << 16), rb = b - __uint_as_float(hi & 0xffff0000u);
+  const bf16x2 l = __builtin_convertvector((f32x2){ra, rb}, bf16x2);
+  lo = __builtin_bit_cast(uint32_t, l);
+}
+
 // grid (8 * n_rgb * ceil(n_chunks * Hkv / 8), 1, batch), block 256.  Workgroups go to the 8 XCDs
 // round-robin by their linear index, so the n_rgb workgroups that stream the SAME keys for
 // different query row groups are placed 8 apart: they run on one XCD and share its L2.
@@ -171,10 +184,13 @@ __global__ __launch_bounds__(256) void tree_attention_kernel(StepMeta m, KvGeom 
       const float m_new = fmaxf(m_run[w], mx);
       const bool any = m_new != -INFINITY;
       const float alpha = (m_run[w] == -INFINITY) ? 0.f : __expf(m_run[w] - m_new);
+      // exp(-inf) = 0 covers the masked keys; a query that has seen no key yet (m_new = -inf)
+      // subtracts 0 instead, so that all of its scores stay -inf and give 0 as well
+      const float m_sub = any ? m_new : 0.f;
       float p[16], psum = 0.f;
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        p[j] = (any && sT[j] != -INFINITY) ? __expf(sT[j] - m_new) : 0.f;
+        p[j] = __expf(sT[j] - m_sub);
         psum += p[j];
       }
       psum += __shfl_xor(psum, 32, 64);
@@ -194,11 +210,10 @@ __global__ __launch_bounds__(256) void tree_attention_kernel(StepMeta m, KvGeom 
         u32x4 pb, pl;  // probabilities as hi + lo bf16 planes
 #pragma unroll
         for (int i2 = 0; i2 < 4; ++i2) {
-          uint16_t h0, l0, h1, l1;
-          split_bf16(p[8 * mm + 2 * i2], h0, l0);
-          split_bf16(p[8 * mm + 2 * i2 + 1], h1, l1);
-          pb[i2] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-          pl[i2] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+          uint32_t hi2, lo2;
+          split_bf16_pair(p[8 * mm + 2 * i2], p[8 * mm + 2 * i2 + 1], hi2, lo2);
+          pb[i2] = hi2;
+          pl[i2] = lo2;
         }
         // matching V^T k-slots: key pairs 8*mm + 2*h, +1, 8*mm + 4 + 2*h, +1
         const uint32_t *vrow = vpb + (8 * mm + 2 * h) * HD + ql;
@@ -366,11 +381,26 @@ hipError_t tree_attention_set_lds_limit() {
   return hipFuncSetAttribute((const void *)tree_attention_kernel<64, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
 }
 
-// Key-chunk size (a multiple of 32) aiming at ~256 workgroups for the longest sequence.
+// Key-chunk size (a multiple of 32).  One sequence: ~256 workgroups (one per compute unit) over
+// its keys.  Several sequences (a batch, or the pieces of a wide prefill pass): if (KV heads x
+// sequences x row-group blocks) already gives a workgroup per compute unit, every sequence is one
+// chunk (measured on the 7B prefill: 23.7 us against 28.8 with two chunks); otherwise the sequences
+// differ in length and there are few heads to spread them, so the chunks are made smaller -- ~1024
+// workgroups if all were as long as the longest, at least 128 keys (one tile per wavefront) -- and
+// the short ones simply need fewer of them (1.1B, 16 utterances: 67 us against 80); the number of
+// chunks stays within what the wide workspace holds (128 / n_kv_heads + 1).
 int tree_attention_chunk_keys(int max_total_keys, int n_kv_heads, int batch, int row_group_blocks) {
-  long want = ((long)max_total_keys * n_kv_heads * batch * row_group_blocks + 255) / 256;
+  const long target = batch > 1 ? 1024 : 256;
+  long want = ((long)max_total_keys * n_kv_heads * batch * row_group_blocks + target - 1) / target;
   long ck = (want + 31) / 32 * 32;
   if (ck < 32) ck = 32;
+  if (batch > 1) {
+    if (ck < 128) ck = 128;
+    if ((long)n_kv_heads * batch * row_group_blocks >= 256) ck = ((long)max_total_keys + 31) / 32 * 32;
+    const long max_chunks = 128 / n_kv_heads + 1;
+    const long ck_min = ((max_total_keys + max_chunks - 1) / max_chunks + 31) / 32 * 32;
+    if (ck < ck_min) ck = ck_min;
+  }
   if (const char *e = getenv("SPECASR_ATTN_CHUNK")) {  // tuning aid: never below the automatic size
     const long v = atol(e) / 32 * 32;
     if (v > ck) ck = v;

@@ -176,15 +176,21 @@ def test_batch_of_ragged_sequences():
     ver.close()
 
 
-def test_batch_above_64_rows_runs_in_sequence_groups_on_the_mfma_path():
-    """Seven bf16 sequences with 150 tree nodes in total (one full 64-node tree): the call is
-    processed as consecutive groups of whole sequences with at most 64 rows each, all on the MFMA
-    kernels; every sequence equals the oracle run on it alone, and tree_forward agrees."""
+@pytest.mark.parametrize("sizes", [
+    (20, 30, 14, 40, 1, 5, 16),      # 126 rows: consecutive groups of whole sequences, <= 64 rows each
+    (20, 30, 14, 64, 1, 5, 16),      # 150 rows: one pass on the wide (tiled GEMM) kernels, 2 row tiles
+    (64, 64, 64, 64, 3, 64, 64),     # 387 rows: wide, 4 row tiles, the last almost empty
+])
+def test_batch_above_64_rows_runs_on_the_mfma_path(sizes):
+    """Seven bf16 sequences with more than 64 tree nodes in total.  Up to 128 rows the call is
+    processed as consecutive groups of whole sequences with at most 64 rows each on the skinny
+    kernels; from 129 rows on as one pass whose projections run on the tiled GEMM.  Either way
+    every sequence equals the oracle run on it alone, tree_forward agrees with verify_tree, and
+    the draft-side read-out equals the oracle's read-out of the same logits."""
     from paper_2507_18181_amd import binding as B
     cfg = wl.MODELS["tiny"]
     w = wl.make_weights(cfg, 91, "bf16")
     rng = np.random.default_rng(92)
-    sizes = (20, 30, 14, 64, 1, 5, 16)
     Ls = [37, 90, 5, 60, 0, 33, 64]
     nb, cap = len(sizes), 160
     ver = _verifier(cfg, w, "bf16", max_nodes=64, capacity=cap, max_batch=nb)
@@ -214,6 +220,13 @@ def test_batch_above_64_rows_runs_in_sequence_groups_on_the_mfma_path():
         got = widen_cache(k2[b, :, :, Ls[b]:Ls[b] + alen])
         assert np.abs(got - want).max() <= TOL_BF16 * np.abs(want).max()
         assert np.all(out["argmax"][b, n:] == -1)
+    ver.set_cache(K, V, Ls)
+    dr = ver.tree_forward_top2(toks, trees, want_logits=True)
+    assert dr["status"] == 0
+    for b in range(nb):
+        n = sizes[b]
+        assert torch.equal(dr["logits"][b, :n], fwd["logits"][b, :n])
+        check_top2(dr["logits"][b].cpu().numpy(), dr["top2"][b].cpu().numpy(), dr["prob"][b].cpu().numpy(), n)
     ver.close()
 
 
