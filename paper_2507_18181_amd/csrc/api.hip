@@ -651,8 +651,9 @@ struct SeqGroup {
 // From kWideMinRows rows on (tuning aid: SPECASR_WIDE_MIN_ROWS) the whole call is ONE group on the
 // wide kernels instead: the weights are streamed once, not once per group.
 int wide_min_rows() {
-  static const int v = [] { const char *e = getenv("SPECASR_WIDE_MIN_ROWS"); const int x = e ? atoi(e) : 129; return x < 65 ? 65 : x; }();
-  return v;
+  const char *e = getenv("SPECASR_WIDE_MIN_ROWS");
+  const int x = e ? atoi(e) : 129;
+  return x < 65 ? 65 : x;
 }
 
 std::vector<SeqGroup> split_call(const specasr_ctx *ctx, const specasr_kv *kv, const specasr_tree *tree,
@@ -746,7 +747,8 @@ specasr_status build_packed(specasr_ctx *ctx) {
     }
   ctx->part_floats = bound;
   // wide passes: more than 64 rows at once -- prefill pieces or the trees of a batch (MFMA attention only)
-  static const bool wide_off = [] { const char *e = getenv("SPECASR_WIDE"); return e && atoi(e) == 0; }();
+  const char *wide_env = getenv("SPECASR_WIDE");  // read at context creation: "0" keeps this context off the wide kernels
+  const bool wide_off = wide_env && atoi(wide_env) == 0;
   if (tree_attention_supported(c.head_dim) && !wide_off) {
     size_t wb = 0;
     const int rows_max = wide_seqs(c.max_batch) * c.max_nodes;

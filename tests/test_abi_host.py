@@ -190,3 +190,15 @@ def test_prefill_and_draft_forward_validate_on_the_host(ctx):
     assert B.specasr_tree_forward_top2(ctx, kv, tree, FAKE, FAKE, None, FAKE, 1024) == B.SPECASR_E_WORKSPACE
     kv2 = B.make_kv(FAKE, FAKE, 100, np.array([100], np.int32))
     assert B.specasr_tree_forward_top2(ctx, kv2, tree, FAKE, FAKE, None, FAKE, wsb) == B.SPECASR_E_KV_OVERFLOW
+
+
+def test_measurement_aids_need_the_mfma_path(ctx):
+    """specasr_profile_stage / specasr_stage_time / specasr_stage_rows: a context without repacked
+    weights (fp32, or no GPU) reports UNSUPPORTED, bad stages and NULL handles are rejected."""
+    assert B.specasr_profile_stage(ctx, 2, 1) == B.SPECASR_E_UNSUPPORTED
+    assert B.specasr_profile_stage(ctx, 7, 1) == B.SPECASR_E_UNSUPPORTED
+    assert B.specasr_profile_stage(None, 2, 1) == B.SPECASR_E_NULL
+    assert B.specasr_stage_time(ctx)[0] == B.SPECASR_E_UNSUPPORTED
+    assert B.specasr_stage_rows(ctx)[0] == B.SPECASR_E_UNSUPPORTED
+    assert B.specasr_stage_rows(None)[0] == B.SPECASR_E_NULL
+    assert B.specasr_uses_mfma(ctx, 200) == 0

@@ -487,6 +487,15 @@ def test_prefill_wide_passes_equal_oracle_prefill(max_nodes, n_audio, n_text):
                    cap=400, max_pos=320)
 
 
+def test_prefill_without_wide_passes_runs_chunks_on_two_lanes(monkeypatch):
+    """A context created with SPECASR_WIDE=0 has no wide buffers: the same long prefixes go through
+    chunks of max_nodes positions, consecutive chunks alternating between two streams that are
+    ordered layer by layer with events.  Same result."""
+    monkeypatch.setenv("SPECASR_WIDE", "0")
+    _check_prefill("bf16", TOL_BF16, 16, n_audio=[250, 100, 64], n_text=[63, 15, 16], L0=[7, 0, 20],
+                   cap=400, max_pos=320)
+
+
 def _check_prefill(dtype, tol, max_nodes, n_audio, n_text, L0, cap, max_pos):
     cfg = wl.MODELS["tiny"]
     w = wl.make_weights(cfg, 97, dtype)
