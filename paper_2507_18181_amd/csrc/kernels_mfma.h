@@ -33,7 +33,7 @@ void launch_gemm_wide(const PackedMatrix &W, const uint16_t *Xp, int rows, float
 int residual_slabs(int d);
 void launch_residual_gain(float *x, const float *part, int n_splits, int rows, int ldp,
                           const void *gain, int d, uint16_t *hb, uint16_t *hb_lo, int nb, float *ssq,
-                          hipStream_t st);
+                          hipStream_t st, int rows_pad = 0);
 void launch_qkv_finish(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
                        const float *part, int n_splits, int ldp, const RowNorm &nrm, int col_k,
                        int col_v, const float2 *cs, float *q, uint16_t *qb, uint16_t *qb_lo, void *kc,

@@ -419,14 +419,13 @@ constexpr int kSlabCols = 32;
 __global__ __launch_bounds__(512) void residual_gain_kernel(float *x, const float *part, int n_splits,
                                                             int rows, int ldp, const uint16_t *gain,
                                                             int d, uint16_t *hb, uint16_t *hb_lo,
-                                                            int nb, float *ssq, int n_slab) {
+                                                            int nb, float *ssq, int n_slab, int rows_pad) {
   const int r = blockIdx.y * 64 + (threadIdx.x >> 3), c = blockIdx.x * kSlabCols + (threadIdx.x & 7) * 4;
   const bool ok = r < rows && c < d;
   float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
   if (ok) {
     float *xr = x + (int64_t)r * d + c;
     v = *reinterpret_cast<const float4 *>(xr);
-    const int rows_pad = part_rows_pad(rows);
     const float *pp = part + part_offset(0, r, c, ldp >> 5, rows_pad);
     const int64_t sstride = (int64_t)ldp * rows_pad;
     int s = 0;
@@ -468,13 +467,16 @@ __global__ __launch_bounds__(512) void residual_gain_kernel(float *x, const floa
 
 int residual_slabs(int d) { return (d + kSlabCols - 1) / kSlabCols; }
 
+// `rows_pad` = row padding of the partial-sum blocks; 0: that of `rows` (differs when x, part and
+// ssq are views that start at a later row of a larger call).
 void launch_residual_gain(float *x, const float *part, int n_splits, int rows, int ldp,
                           const void *gain, int d, uint16_t *hb, uint16_t *hb_lo, int nb, float *ssq,
-                          hipStream_t st) {
+                          hipStream_t st, int rows_pad) {
   const int n_slab = residual_slabs(d);
+  if (rows_pad <= 0) rows_pad = part_rows_pad(rows);
   const int per_block = rows < 64 ? rows : 64;
   dim3 grid(n_slab, (rows + 63) / 64);
-  residual_gain_kernel<<<grid, ((per_block + 7) / 8) * 64, 0, st>>>(x, part, n_splits, rows, ldp, (const uint16_t *)gain, d, hb, hb_lo, nb, ssq, n_slab);
+  residual_gain_kernel<<<grid, ((per_block + 7) / 8) * 64, 0, st>>>(x, part, n_splits, rows, ldp, (const uint16_t *)gain, d, hb, hb_lo, nb, ssq, n_slab, rows_pad);
 }
 
 // q, k, v = sum of partials; rotary embedding at the node's depth position (Sec. II-B: each
