@@ -113,13 +113,19 @@ __global__ __launch_bounds__(256) void tree_attention_kernel(StepMeta m, KvGeom 
   const uint16_t *kbase = kc + g.row(seq, layer, kvh, 0);
   const uint16_t *vbase = vc + g.row(seq, layer, kvh, 0);
 
-  // One 32-key tile in flight while the previous one is computed (register double buffer):
-  // K as A-operand registers, V as raw row pairs that are interleaved into LDS when consumed.
+  // One register set for the tile in flight: K as A-operand registers, V as raw row pairs that are
+  // interleaved into LDS when consumed.  Each half is requested again for the wavefront's NEXT
+  // tile as soon as the current tile has consumed it (V after its copy to LDS, K after the last
+  // QK^T product), so the loads have the rest of the tile's work to arrive -- and the kernel keeps
+  // one tile's worth of staging registers instead of two.
   constexpr int VI = HD / 32;  // (key pair, 8-column group) items per lane
-  auto issue = [&](int t0, u32x4 (&kreg)[KK], u32x4 (&va)[VI], u32x4 (&vb)[VI]) {
+  u32x4 kreg[KK], va[VI], vb[VI];
+  auto issue_k = [&](int t0) {
     const uint16_t *kp = kbase + (int64_t)min(t0 + ql, T - 1) * HD + 8 * h;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) kreg[kk] = *reinterpret_cast<const u32x4 *>(kp + 16 * kk);
+  };
+  auto issue_v = [&](int t0) {
 #pragma unroll
     for (int x = 0; x < VI; ++x) {
       const int it = lane + 64 * x;
@@ -129,7 +135,7 @@ __global__ __launch_bounds__(256) void tree_attention_kernel(StepMeta m, KvGeom 
       vb[x] = *reinterpret_cast<const u32x4 *>(vbase + (int64_t)k1 * HD + 8 * cg);
     }
   };
-  auto compute = [&](int t0, uint32_t *vpb, const u32x4 (&kreg)[KK], const u32x4 (&va)[VI], const u32x4 (&vb)[VI]) {
+  auto compute = [&](int t0, uint32_t *vpb, bool more) {
     // V tile into LDS, two keys interleaved per 32-bit word (low half = even key)
 #pragma unroll
     for (int x = 0; x < VI; ++x) {
@@ -151,6 +157,7 @@ __global__ __launch_bounds__(256) void tree_attention_kernel(StepMeta m, KvGeom 
     }
     // only this wavefront reads the tile back: its own LDS operations stay in program order
     __builtin_amdgcn_wave_barrier();
+    if (more) issue_v(t0 + 128);
 #pragma unroll
     for (int w = 0; w < RGW; ++w) {
       f32x16 sT, sT2;  // hi and lo query planes on separate accumulators (independent chains)
@@ -163,6 +170,7 @@ __global__ __launch_bounds__(256) void tree_attention_kernel(StepMeta m, KvGeom 
         sT2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[kk]),
                                                       __builtin_bit_cast(bf16x8, qlo[w][kk]), sT2, 0, 0, 0);
       }
+      if (w == RGW - 1 && more) issue_k(t0 + 128);
       // lane holds, for query ql, the keys t0 + 8*(j/4) + 4*h + j%4
       float mx = -INFINITY;
       if (t0 + 32 <= L) {  // tile inside the prefix: every key visible to every valid query
@@ -233,16 +241,13 @@ __global__ __launch_bounds__(256) void tree_attention_kernel(StepMeta m, KvGeom 
     }
   };
 
-  u32x4 kA[KK], vaA[VI], vbA[VI], kB[KK], vaB[VI], vbB[VI];
   const int t_first = t_begin + 32 * wave;  // this wavefront's tiles: t_first, +128, +256, ...
-  if (t_first < t_end) issue(t_first, kA, vaA, vbA);
-  for (int t0 = t_first; t0 < t_end; t0 += 256) {
-    const bool hasB = t0 + 128 < t_end;
-    if (hasB) issue(t0 + 128, kB, vaB, vbB);
-    compute(t0, vp, kA, vaA, vbA);
-    if (t0 + 256 < t_end) issue(t0 + 256, kA, vaA, vbA);
-    if (hasB) compute(t0 + 128, vp + 16 * HD, kB, vaB, vbB);
+  if (t_first < t_end) {
+    issue_k(t_first);
+    issue_v(t_first);
   }
+  int vbuf = 0;  // the two LDS tiles of the wavefront alternate
+  for (int t0 = t_first; t0 < t_end; t0 += 128, vbuf ^= 1) compute(t0, vp + vbuf * (16 * HD), t0 + 128 < t_end);
 
   // merge the four wavefronts: everything to LDS in register layout, then wavefront cb reduces
   // column block cb and writes the workgroup's partial result
@@ -354,7 +359,10 @@ static void launch_attn_hd(const StepMeta &m, const ModelDims &md, const KvGeom 
     const size_t mg = (size_t)4 * rgw * (HD / 32) * 4096 + (size_t)4 * rgw * 32 * 2 * 4;
     return vt > mg ? vt : mg;
   };
-  if (!pair || HD > 64) {
+  if constexpr (HD > 64) {
+    dim3 grid((n_chunks * md.n_kv_heads + 7) / 8 * 8 * row_groups, 1, m.batch);
+    tree_attention_kernel<HD, 1><<<grid, 256, lds_bytes(1), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, row_groups, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, n_chunks, o_part, ml_part);
+  } else if (!pair) {
     dim3 grid((n_chunks * md.n_kv_heads + 7) / 8 * 8 * row_groups, 1, m.batch);
     tree_attention_kernel<HD, 1><<<grid, 256, lds_bytes(1), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, row_groups, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, n_chunks, o_part, ml_part);
   } else {
@@ -372,9 +380,7 @@ int tree_attention_max_chunks(int n_kv_heads) { return 256 / n_kv_heads + 2; }
 
 hipError_t tree_attention_set_lds_limit() {
   const int big = 4 * 2 * 4 * 4096 + 4 * 2 * 32 * 2 * 4;  // RGW = 2, head_dim 128
-  hipError_t e = hipFuncSetAttribute((const void *)tree_attention_kernel<128, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute((const void *)tree_attention_kernel<128, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
+  hipError_t e = hipFuncSetAttribute((const void *)tree_attention_kernel<128, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute((const void *)tree_attention_kernel<64, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
   if (e != hipSuccess) return e;
@@ -414,12 +420,13 @@ void launch_tree_attention(const StepMeta &m, const ModelDims &md, const KvGeom 
                            float *ml_part, uint16_t *out, uint16_t *out_lo, int nb, hipStream_t st) {
   const int G = md.n_heads / md.n_kv_heads;
   const int row_groups = (G * max_seq_nodes + 31) / 32;
-  // Two query row groups per workgroup halve the key traffic, but only where their accumulators
-  // fit the register file (head_dim 64) and the key range is long enough to matter: with at most
-  // one tile per wavefront a second row group would just run behind the first on the same
-  // wavefront.
-  bool pair = row_groups > 1 && md.head_dim <= 64;
-  if (pair && tree_attention_chunk_keys(max_total_keys, md.n_kv_heads, m.batch, row_groups) <= 128) pair = false;
+  // Two query row groups per workgroup halve the key traffic (head_dim 64 only: their accumulators
+  // fit the register file) -- but the keys of a head are L2 hits after their first use and the
+  // kernel is bound by its softmax arithmetic, so one row group per workgroup, twice the
+  // workgroups and half the registers measured faster wherever it was tried (16 utterances on the
+  // 1.1B model: 38 against 43 us).  Kept as a tuning aid: SPECASR_ATTN_PAIR=1.
+  bool pair = false;
+  if (const char *e = getenv("SPECASR_ATTN_PAIR")) pair = atoi(e) != 0 && row_groups > 1 && md.head_dim <= 64;
   const int n_rgb = pair ? (row_groups + 1) / 2 : row_groups;
   const int ck = tree_attention_chunk_keys(max_total_keys, md.n_kv_heads, m.batch, n_rgb);
   const int n_chunks = (max_total_keys + ck - 1) / ck;
