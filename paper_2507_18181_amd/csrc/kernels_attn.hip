@@ -60,7 +60,9 @@ __global__ __launch_bounds__(256) void tree_attention_kernel(StepMeta m, KvGeom 
                                                             const uint16_t *__restrict__ vc,
                                                             int chunk_keys, int n_chunks,
                                                             float *__restrict__ o_part,
-                                                            float *__restrict__ ml_part) {
+                                                            float *__restrict__ ml_part,
+                                                            uint16_t *__restrict__ out,
+                                                            uint16_t *__restrict__ out_lo, int nb) {
   constexpr int KK = HD / 16;  // MFMA k-steps across the head dimension
   constexpr int CB = HD / 32;  // 32-wide output column blocks
   // LDS: per wavefront two V tiles [key pair][column] (low half = even key); reused afterwards
@@ -288,6 +290,23 @@ __global__ __launch_bounds__(256) void tree_attention_kernel(StepMeta m, KvGeom 
       }
       if (!valid[w]) continue;
       // O^T lane layout = query column ql, output columns 32*cb + 8*(j/4) + 4*h + j%4
+      if (out != nullptr) {
+        // every sequence is a single chunk: this IS the result -- normalise and write the packed
+        // hi/lo planes the output projection reads (what the merge kernel would do with one chunk)
+        const int col0 = out_head[w] * HD + 32 * cb + 4 * h;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          uint16_t hi4[4], lo4[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) split_bf16(acc[4 * q4 + i] / Lsum, hi4[i], lo4[i]);
+          const int64_t po = packed_act_offset(out_row[w], col0 + 8 * q4, nb);
+          *reinterpret_cast<uint2 *>(out + po) =
+              make_uint2((uint32_t)hi4[0] | ((uint32_t)hi4[1] << 16), (uint32_t)hi4[2] | ((uint32_t)hi4[3] << 16));
+          *reinterpret_cast<uint2 *>(out_lo + po) =
+              make_uint2((uint32_t)lo4[0] | ((uint32_t)lo4[1] << 16), (uint32_t)lo4[2] | ((uint32_t)lo4[3] << 16));
+        }
+        continue;
+      }
       const int64_t base = ((int64_t)chunk * rows + out_row[w]) * H + out_head[w];
       float *op = o_part + base * HD + 32 * cb + 4 * h;
 #pragma unroll
@@ -353,6 +372,7 @@ static void launch_attn_hd(const StepMeta &m, const ModelDims &md, const KvGeom 
                            hipStream_t st) {
   const int G = md.n_heads / md.n_kv_heads;
   const int row_groups = (G * max_seq_nodes + 31) / 32;
+  const bool direct = n_chunks == 1;  // nothing to merge: the attention kernel writes the final planes
   // LDS: 4 wavefronts x 2 V tiles, reused for the merge (4 x RGW x HD/32 x 4 KB + (m, l))
   auto lds_bytes = [](int rgw) {
     const size_t vt = (size_t)4 * 2 * 16 * HD * 4;
@@ -361,15 +381,16 @@ static void launch_attn_hd(const StepMeta &m, const ModelDims &md, const KvGeom 
   };
   if constexpr (HD > 64) {
     dim3 grid((n_chunks * md.n_kv_heads + 7) / 8 * 8 * row_groups, 1, m.batch);
-    tree_attention_kernel<HD, 1><<<grid, 256, lds_bytes(1), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, row_groups, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, n_chunks, o_part, ml_part);
+    tree_attention_kernel<HD, 1><<<grid, 256, lds_bytes(1), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, row_groups, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, n_chunks, o_part, ml_part, direct ? out : nullptr, direct ? out_lo : nullptr, nb);
   } else if (!pair) {
     dim3 grid((n_chunks * md.n_kv_heads + 7) / 8 * 8 * row_groups, 1, m.batch);
-    tree_attention_kernel<HD, 1><<<grid, 256, lds_bytes(1), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, row_groups, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, n_chunks, o_part, ml_part);
+    tree_attention_kernel<HD, 1><<<grid, 256, lds_bytes(1), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, row_groups, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, n_chunks, o_part, ml_part, direct ? out : nullptr, direct ? out_lo : nullptr, nb);
   } else {
     const int n_rgb = (row_groups + 1) / 2;
     dim3 grid((n_chunks * md.n_kv_heads + 7) / 8 * 8 * n_rgb, 1, m.batch);
-    tree_attention_kernel<HD, 2><<<grid, 256, lds_bytes(2), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, n_rgb, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, n_chunks, o_part, ml_part);
+    tree_attention_kernel<HD, 2><<<grid, 256, lds_bytes(2), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, n_rgb, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, n_chunks, o_part, ml_part, direct ? out : nullptr, direct ? out_lo : nullptr, nb);
   }
+  if (direct) return;
   dim3 mgrid(md.n_heads, m.rows);
   tree_attention_merge_kernel<<<mgrid, HD, 0, st>>>(m, md.n_heads, HD, chunk_keys, o_part, ml_part, out, out_lo, nb);
 }

@@ -536,17 +536,158 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(StepMeta m, KvGeom g, i
   }
 }
 
+// The same for many rows (a wide pass, bf16 queries for the MFMA attention): one workgroup per
+// (head, group of 32 rows); thread t takes row t/8 and the rotary pairs j = 4*(t%8)..+3 (+32 per
+// further band of the half head), so that every load is 16 bytes per thread out of a contiguous
+// 4 KB band block and every store 8 bytes of 4 consecutive bf16.
+__global__ __launch_bounds__(256) void qkv_finish_wide_kernel(StepMeta m, KvGeom g, int layer, int H, int Hkv,
+                                                              int hd, const float *part, int n_splits,
+                                                              int ldp, RowNorm nrm, int col_k, int col_v,
+                                                              const float2 *cs, uint16_t *qb,
+                                                              uint16_t *qb_lo, float qscale, uint16_t *kc,
+                                                              uint16_t *vc) {
+  const int rows = m.rows, half = hd / 2;
+  const int a = blockIdx.x, r = blockIdx.y * 32 + (threadIdx.x >> 3), sub = threadIdx.x & 7;
+  const int rr = r < rows ? r : rows - 1;
+  float ss = 0.f;
+  {
+    const float *sq = nrm.ssq + (int64_t)rr * nrm.n_slab;
+    int i = sub;
+    for (; i + 56 < nrm.n_slab; i += 64) {  // 8 independent loads in flight
+      const float a0 = sq[i], a1 = sq[i + 8], a2 = sq[i + 16], a3 = sq[i + 24];
+      const float a4 = sq[i + 32], a5 = sq[i + 40], a6 = sq[i + 48], a7 = sq[i + 56];
+      ss += ((a0 + a1) + (a2 + a3)) + ((a4 + a5) + (a6 + a7));
+    }
+    for (; i < nrm.n_slab; i += 8) ss += sq[i];
+  }
+  ss += __shfl_xor(ss, 1, 64);
+  ss += __shfl_xor(ss, 2, 64);
+  ss += __shfl_xor(ss, 4, 64);
+  const float rs = 1.0f / sqrtf(ss / (float)nrm.d + nrm.eps);
+  if (r >= rows) return;
+  const int rows_pad = part_rows_pad(rows), n_bands = ldp >> 5;
+  auto sum4 = [&](int col) {  // sum over the splits of 4 consecutive columns of row r, times 1/rms
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+    for (int s = 0; s < n_splits; ++s) {
+      const float4 p = *reinterpret_cast<const float4 *>(part + part_offset(s, r, col, n_bands, rows_pad));
+      v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    }
+    v.x *= rs; v.y *= rs; v.z *= rs; v.w *= rs;
+    return v;
+  };
+  auto pack4 = [](const float (&y)[4]) {
+    return make_uint2((uint32_t)f32_to_bf16_bits(y[0]) | ((uint32_t)f32_to_bf16_bits(y[1]) << 16),
+                      (uint32_t)f32_to_bf16_bits(y[2]) | ((uint32_t)f32_to_bf16_bits(y[3]) << 16));
+  };
+  const bool is_q = a < H;
+  const int b = a - H;
+  const int c0 = is_q ? a * hd : col_k + b * hd;
+  for (int j = sub * 4; j < half; j += 32) {
+    const float4 x0 = sum4(c0 + j), x1 = sum4(c0 + j + half);
+    const float4 cs01 = *reinterpret_cast<const float4 *>(cs + (int64_t)r * half + j);       // (cos, sin) of j, j+1
+    const float4 cs23 = *reinterpret_cast<const float4 *>(cs + (int64_t)r * half + j + 2);   // ... of j+2, j+3
+    const float co[4] = {cs01.x, cs01.z, cs23.x, cs23.z}, si[4] = {cs01.y, cs01.w, cs23.y, cs23.w};
+    const float a0[4] = {x0.x, x0.y, x0.z, x0.w}, a1[4] = {x1.x, x1.y, x1.z, x1.w};
+    float y0[4], y1[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      y0[i] = a0[i] * co[i] - a1[i] * si[i];
+      y1[i] = a1[i] * co[i] + a0[i] * si[i];
+    }
+    if (is_q) {
+      const int64_t o = ((int64_t)r * H + a) * hd + j;
+      uint16_t h0[4], l0[4], h1[4], l1[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        split_bf16(y0[i] * qscale, h0[i], l0[i]);
+        split_bf16(y1[i] * qscale, h1[i], l1[i]);
+      }
+      auto pk = [](const uint16_t (&v)[4]) { return make_uint2((uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16)); };
+      *reinterpret_cast<uint2 *>(qb + o) = pk(h0);
+      *reinterpret_cast<uint2 *>(qb_lo + o) = pk(l0);
+      *reinterpret_cast<uint2 *>(qb + o + half) = pk(h1);
+      *reinterpret_cast<uint2 *>(qb_lo + o + half) = pk(l1);
+    } else {
+      const float4 v0 = sum4(col_v + b * hd + j), v1 = sum4(col_v + b * hd + j + half);
+      const int64_t base = g.row(m.seq[r], layer, b, m.slot[r]);
+      *reinterpret_cast<uint2 *>(kc + base + j) = pack4(y0);
+      *reinterpret_cast<uint2 *>(kc + base + j + half) = pack4(y1);
+      const float w0[4] = {v0.x, v0.y, v0.z, v0.w}, w1[4] = {v1.x, v1.y, v1.z, v1.w};
+      *reinterpret_cast<uint2 *>(vc + base + j) = pack4(w0);
+      *reinterpret_cast<uint2 *>(vc + base + j + half) = pack4(w1);
+    }
+  }
+}
+
 void launch_qkv_finish(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
                        const float *part, int n_splits, int ldp, const RowNorm &nrm, int col_k,
                        int col_v, const float2 *cs, float *q, uint16_t *qb, uint16_t *qb_lo, void *kc,
                        void *vc, hipStream_t st) {
+  if (m.rows > 64 && qb != nullptr && md.head_dim % 64 == 0) {
+    dim3 wgrid(md.n_heads + md.n_kv_heads, (m.rows + 31) / 32);
+    qkv_finish_wide_kernel<<<wgrid, 256, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, md.head_dim, part, n_splits, ldp, nrm, col_k, col_v, cs, qb, qb_lo, 1.0f / sqrtf((float)md.head_dim), (uint16_t *)kc, (uint16_t *)vc);
+    return;
+  }
   const int items = (md.n_heads + md.n_kv_heads) * (md.head_dim / 2);
   dim3 grid((items + 255) / 256, m.rows);
   qkv_finish_kernel<<<grid, 256, 0, st>>>(m, g, layer, md.n_heads, md.n_kv_heads, md.head_dim, part, n_splits, ldp, nrm, col_k, col_v, cs, q, qb, qb_lo, 1.0f / sqrtf((float)md.head_dim), (uint16_t *)kc, (uint16_t *)vc);
 }
 
-// t[r][f] = bf16( silu(sum_s gate) * (sum_s up) ); gate at column f, up at column col_up + f
+// t[r][f] = bf16 planes of silu(sum_s gate) * (sum_s up); gate at column f, up at column col_up + f.
+// One workgroup per (band of 32 features, group of 32 rows): in the partial-sum layout that is one
+// contiguous 4 KB block of gate and one of up per split, read with 16 bytes per thread (thread t:
+// row t/8, features 4*(t%8)..+3), and one contiguous 1 KB block per k-step and plane on the way
+// out.  The 8 threads of a row also share the sum over its norm slabs.
 __global__ __launch_bounds__(256) void swiglu_finish_kernel(const float *part, int n_splits, int rows,
+                                                            int ldp, RowNorm nrm, int col_up, int F,
+                                                            uint16_t *t, uint16_t *t_lo, int nb) {
+  const int r = blockIdx.y * 32 + (threadIdx.x >> 3), sub = threadIdx.x & 7;
+  const int f = blockIdx.x * 32 + sub * 4;
+  const bool ok = r < rows && f < F;
+  const int rr = r < rows ? r : rows - 1;
+  // 1 / rms of the row: the 8 threads of a row add up its slab sums of squares
+  float ss = 0.f;
+  {
+    const float *sq = nrm.ssq + (int64_t)rr * nrm.n_slab;
+    int i = sub;
+    for (; i + 56 < nrm.n_slab; i += 64) {  // 8 independent loads in flight
+      const float a0 = sq[i], a1 = sq[i + 8], a2 = sq[i + 16], a3 = sq[i + 24];
+      const float a4 = sq[i + 32], a5 = sq[i + 40], a6 = sq[i + 48], a7 = sq[i + 56];
+      ss += ((a0 + a1) + (a2 + a3)) + ((a4 + a5) + (a6 + a7));
+    }
+    for (; i < nrm.n_slab; i += 8) ss += sq[i];
+  }
+  ss += __shfl_xor(ss, 1, 64);
+  ss += __shfl_xor(ss, 2, 64);
+  ss += __shfl_xor(ss, 4, 64);
+  const float rs = 1.0f / sqrtf(ss / (float)nrm.d + nrm.eps);
+  if (!ok) return;
+  float4 gt = make_float4(0.f, 0.f, 0.f, 0.f), up = gt;
+  const int rows_pad = part_rows_pad(rows), n_bands = ldp >> 5;
+#pragma unroll 4
+  for (int s = 0; s < n_splits; ++s) {
+    const float4 a = *reinterpret_cast<const float4 *>(part + part_offset(s, r, f, n_bands, rows_pad));
+    const float4 b = *reinterpret_cast<const float4 *>(part + part_offset(s, r, col_up + f, n_bands, rows_pad));
+    gt.x += a.x; gt.y += a.y; gt.z += a.z; gt.w += a.w;
+    up.x += b.x; up.y += b.y; up.z += b.z; up.w += b.w;
+  }
+  auto act = [rs](float gv, float uv) { gv *= rs; return gv / (1.0f + __expf(-gv)) * (uv * rs); };
+  const float y[4] = {act(gt.x, up.x), act(gt.y, up.y), act(gt.z, up.z), act(gt.w, up.w)};
+  uint16_t hi[4], lo[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) split_bf16(y[i], hi[i], lo[i]);
+  const int64_t po = packed_act_offset(r, f, nb);
+  *reinterpret_cast<uint2 *>(t + po) =
+      make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+  *reinterpret_cast<uint2 *>(t_lo + po) =
+      make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+}
+
+// The same for few rows (<= 64): one workgroup per (1024 features, row), one sum over the norm slabs
+// per wavefront -- with so few rows the band-block mapping above re-reads the slab sums too often
+// (7B, 32 rows: 5.5 against 6.8 us).
+__global__ __launch_bounds__(256) void swiglu_finish_rows_kernel(const float *part, int n_splits, int rows,
                                                             int ldp, RowNorm nrm, int col_up, int F,
                                                             uint16_t *t, uint16_t *t_lo, int nb) {
   const int r = blockIdx.y;
@@ -576,7 +717,12 @@ __global__ __launch_bounds__(256) void swiglu_finish_kernel(const float *part, i
 
 void launch_swiglu_finish(const float *part, int n_splits, int rows, int ldp, const RowNorm &nrm,
                           int col_up, int F, uint16_t *t, uint16_t *t_lo, int nb, hipStream_t st) {
-  dim3 grid((F / 4 + 255) / 256, rows);
+  if (rows <= 64) {
+    dim3 grid((F / 4 + 255) / 256, rows);
+    swiglu_finish_rows_kernel<<<grid, 256, 0, st>>>(part, n_splits, rows, ldp, nrm, col_up, F, t, t_lo, nb);
+    return;
+  }
+  dim3 grid((F + 31) / 32, (rows + 31) / 32);
   swiglu_finish_kernel<<<grid, 256, 0, st>>>(part, n_splits, rows, ldp, nrm, col_up, F, t, t_lo, nb);
 }
 
