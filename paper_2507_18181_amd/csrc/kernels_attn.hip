@@ -421,6 +421,9 @@ int tree_attention_chunk_keys(int max_total_keys, int n_kv_heads, int batch, int
   long want = ((long)max_total_keys * n_kv_heads * batch * row_group_blocks + target - 1) / target;
   long ck = (want + 31) / 32 * 32;
   if (ck < 32) ck = 32;
+  // a short single sequence: one chunk, the attention kernel writes the result itself and no merge
+  // kernel runs (1.1B, ~360 keys: 1.536 against 1.555 ms per forward; at 842 keys it loses)
+  if (batch == 1 && max_total_keys <= 512) ck = 512;
   if (batch > 1) {
     if (ck < 128) ck = 128;
     if ((long)n_kv_heads * batch * row_group_blocks >= 256) ck = ((long)max_total_keys + 31) / 32 * 32;
