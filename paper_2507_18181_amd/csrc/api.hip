@@ -561,6 +561,13 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
       while (S > 1 && (size_t)S * pm[i]->ldo * part_rows_pad(R) > ctx->wide_part_floats) S /= 2;
       pls[i]->n_splits = S;
     }
+    if (const char *e = getenv("SPECASR_WIDE_SPLITS")) {  // tuning aid: "qkv,o,gate_up,down,lm_head" split counts
+      int v[5] = {0, 0, 0, 0, 0};
+      sscanf(e, "%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4]);
+      for (int i = 0; i < 5; ++i)
+        if (v[i] >= 1 && v[i] <= pm[i]->ksteps && (size_t)v[i] * pm[i]->ldo * part_rows_pad(R) <= ctx->wide_part_floats)
+          pls[i]->n_splits = v[i];
+    }
   }
 
   if (const char *e = wide ? nullptr : getenv("SPECASR_GEMM_SPLITS")) {  // tuning aid: "qkv,o,gate_up,down,lm_head" split counts

@@ -369,17 +369,27 @@ __global__ __launch_bounds__(256, 2) void gemm_wide_kernel(const u32x4 *__restri
 
 int wide_row_groups(int rows) { return (rows + 32 * kWideTileGroups - 1) / (32 * kWideTileGroups) * kWideTileGroups; }
 
-// k-split of a wide GEMM: enough workgroups for two per compute unit, as long as a split keeps
-// >= 8 k-steps and the partial sums (written here, read again by the consumer) stay below
-// ~100 MB -- measured on the 7B shapes, beyond that the extra traffic costs more than the
-// fuller machine gains.
+// k-split S of a wide GEMM (any integer, each split >= 8 k-steps), from a cost model fitted to
+// measurements on MI355X, in microseconds: the workgroups spread round-robin over the compute
+// units, which work them off two at a time; a workgroup costs 4 us of prologue and epilogue plus
+// 0.45 us of its compute unit per k-step, 0.53 when it runs there alone (an odd one left over at
+// the end, or fewer workgroups than compute units); every split writes the output once as fp32
+// partial sums that the consumer reads again (0.3 us per MB).  E.g. gate|up of the 1.1B model at
+// 384 rows has 132 tiles: S = 3 fills the 512 workgroup slots in one go (4.54 ms per call),
+// S = 4 needs a second, almost empty round (4.97 ms).
 int wide_gemm_splits(int n_bands, int ksteps, int rows, int n_cu) {
   const int64_t tiles = (int64_t)((n_bands + kWideTileBands - 1) / kWideTileBands) * (wide_row_groups(rows) / kWideTileGroups);
-  int S = 1;
-  while (S < 8 && tiles * S < 2 * n_cu && ksteps / (2 * S) >= 8) S *= 2;
-  const int64_t out_bytes = (int64_t)n_bands * 32 * part_rows_pad(rows) * 4;
-  while (S > 1 && S * out_bytes > (100ll << 20)) S /= 2;
-  return S;
+  const double out_mb = (double)n_bands * 32 * part_rows_pad(rows) * 4 / 1e6;
+  int best = 1;
+  double best_cost = 1e300;
+  for (int S = 1; S <= 16 && ksteps / S >= 8; ++S) {
+    const int64_t wgs = tiles * S, per_cu = (wgs + n_cu - 1) / n_cu;
+    const double len = (double)ksteps / S;
+    const double pairs = wgs <= n_cu ? 0.0 : (double)(per_cu / 2), alone = wgs <= n_cu ? 1.0 : (double)(per_cu % 2);
+    const double cost = pairs * 2.0 * (len * 0.45 + 4.0) + alone * (len * 0.53 + 4.0) + S * out_mb * 0.3;
+    if (cost < best_cost) { best_cost = cost; best = S; }
+  }
+  return best;
 }
 
 template <int STAGE>
