@@ -133,12 +133,24 @@ struct RowNorm {
   float eps;  // added to the mean square inside the root
 };
 // 1 / rms of residual row r from the slab sums of squares (eps inside the root, Sec. II-A's decoder
-// block).  Every lane of the calling wavefront must be active; all lanes get the same value.
+// block), in two steps so that a kernel can have its own loads in flight together with these:
+// row_ssq_lane issues the loads of this lane's share (up to 4 at once) and adds them up;
+// row_rms_finish sums over the wavefront.  Every lane of the calling wavefront must be active in
+// row_rms_finish; all lanes get the same value.
+__device__ __forceinline__ float row_ssq_lane(const RowNorm &nrm, int r) {
+  const float *p = nrm.ssq + (int64_t)r * nrm.n_slab;
+  const int i = threadIdx.x & 63, n = nrm.n_slab;
+  const float v0 = i < n ? p[i] : 0.f, v1 = i + 64 < n ? p[i + 64] : 0.f;
+  const float v2 = i + 128 < n ? p[i + 128] : 0.f, v3 = i + 192 < n ? p[i + 192] : 0.f;
+  float s = (v0 + v1) + (v2 + v3);
+  for (int k = i + 256; k < n; k += 64) s += p[k];
+  return s;
+}
+__device__ __forceinline__ float row_rms_finish(const RowNorm &nrm, float lane_ssq) {
+  return 1.0f / sqrtf(wave_sum(lane_ssq) / (float)nrm.d + nrm.eps);
+}
 __device__ __forceinline__ float row_rms_scale(const RowNorm &nrm, int r) {
-  float s = 0.f;
-  for (int i = threadIdx.x & 63; i < nrm.n_slab; i += 64) s += nrm.ssq[(int64_t)r * nrm.n_slab + i];
-  s = wave_sum(s);
-  return 1.0f / sqrtf(s / (float)nrm.d + nrm.eps);
+  return row_rms_finish(nrm, row_ssq_lane(nrm, r));
 }
 
 }  // namespace specasr

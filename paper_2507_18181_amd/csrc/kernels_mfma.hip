@@ -500,9 +500,10 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(StepMeta m, KvGeom g, i
                                                          uint16_t *qb_lo, float qscale, uint16_t *kc,
                                                          uint16_t *vc) {
   const int r = blockIdx.y, half = hd / 2, rows = m.rows;
-  const int idx = blockIdx.x * 256 + threadIdx.x;
-  const float rs = row_rms_scale(nrm, r);
-  if (idx >= (H + Hkv) * half) return;
+  const int idx0 = blockIdx.x * 256 + threadIdx.x, n_items = (H + Hkv) * half;
+  const bool live = idx0 < n_items;
+  const int idx = live ? idx0 : n_items - 1;  // surplus threads of the last block repeat its last item, without stores
+  const float lane_ssq = row_ssq_lane(nrm, r);  // in flight together with the partial sums below
   const int a = idx / half, j = idx - a * half;
   const float2 c = cs[(int64_t)r * half + j];
   const int rows_pad = part_rows_pad(rows);
@@ -518,11 +519,16 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(StepMeta m, KvGeom g, i
       const float v0 = q[at(c0)], v1 = q[at(c1)], v2 = q[at(c2)], v3 = q[at(c3)];
       out[0] += v0; out[1] += v1; out[2] += v2; out[3] += v3;
     }
-    out[0] *= rs; out[1] *= rs; out[2] *= rs; out[3] *= rs;
   };
-  if (a < H) {
-    float t[4];
+  float t[4];
+  if (a < H)
     val4(a * hd + j, a * hd + j + half, a * hd + j, a * hd + j + half, t);
+  else
+    val4(col_k + (a - H) * hd + j, col_k + (a - H) * hd + j + half, col_v + (a - H) * hd + j, col_v + (a - H) * hd + j + half, t);
+  const float rs = row_rms_finish(nrm, lane_ssq);
+  if (!live) return;
+  t[0] *= rs; t[1] *= rs; t[2] *= rs; t[3] *= rs;
+  if (a < H) {
     const float x0 = t[0], x1 = t[1];
     const float y0 = x0 * c.x - x1 * c.y, y1 = x1 * c.x + x0 * c.y;
     const int64_t o = ((int64_t)r * H + a) * hd + j;
@@ -535,8 +541,6 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(StepMeta m, KvGeom g, i
     }
   } else {
     const int b = a - H;
-    float t[4];
-    val4(col_k + b * hd + j, col_k + b * hd + j + half, col_v + b * hd + j, col_v + b * hd + j + half, t);
     const float x0 = t[0], x1 = t[1];
     const int64_t base = g.row(m.seq[r], layer, b, m.slot[r]);
     kc[base + j] = f32_to_bf16_bits(x0 * c.x - x1 * c.y);
@@ -702,17 +706,20 @@ __global__ __launch_bounds__(256) void swiglu_finish_rows_kernel(const float *pa
                                                             uint16_t *t, uint16_t *t_lo, int nb) {
   const int r = blockIdx.y;
   const int f = (blockIdx.x * 256 + threadIdx.x) * 4;
-  const float rs = row_rms_scale(nrm, r);
-  if (f >= F) return;
+  const float lane_ssq = row_ssq_lane(nrm, r);  // in flight together with the partial sums below
   float4 gt = make_float4(0.f, 0.f, 0.f, 0.f), up = gt;
   const int rows_pad = part_rows_pad(rows), n_bands = ldp >> 5;
+  if (f < F) {
 #pragma unroll 4
-  for (int s = 0; s < n_splits; ++s) {
-    const float4 a = *reinterpret_cast<const float4 *>(part + part_offset(s, r, f, n_bands, rows_pad));
-    const float4 b = *reinterpret_cast<const float4 *>(part + part_offset(s, r, col_up + f, n_bands, rows_pad));
-    gt.x += a.x; gt.y += a.y; gt.z += a.z; gt.w += a.w;
-    up.x += b.x; up.y += b.y; up.z += b.z; up.w += b.w;
+    for (int s = 0; s < n_splits; ++s) {
+      const float4 a = *reinterpret_cast<const float4 *>(part + part_offset(s, r, f, n_bands, rows_pad));
+      const float4 b = *reinterpret_cast<const float4 *>(part + part_offset(s, r, col_up + f, n_bands, rows_pad));
+      gt.x += a.x; gt.y += a.y; gt.z += a.z; gt.w += a.w;
+      up.x += b.x; up.y += b.y; up.z += b.z; up.w += b.w;
+    }
   }
+  const float rs = row_rms_finish(nrm, lane_ssq);
+  if (f >= F) return;
   auto act = [rs](float gv, float uv) { gv *= rs; return gv / (1.0f + __expf(-gv)) * (uv * rs); };
   const float y[4] = {act(gt.x, up.x), act(gt.y, up.y), act(gt.z, up.z), act(gt.w, up.w)};
   uint16_t hi[4], lo[4];
