@@ -579,6 +579,54 @@ def test_attention_shapes_bf16(shape):
 
 
 @pytest.mark.parametrize("shape", [
+    dict(n_heads=2, n_kv_heads=2, head_dim=128),                      # head_dim 128: two bands per rotary half
+    dict(n_heads=8, n_kv_heads=1, head_dim=64, d_model=512),          # 8 query heads on one KV head
+    dict(n_heads=4, n_kv_heads=2, head_dim=128, d_model=272, d_ffn=1008, vocab=1003),  # 17 / 63 k-steps, partial tiles everywhere
+    dict(n_heads=1, n_kv_heads=1, head_dim=64, d_model=48, d_ffn=80, vocab=97),        # 3 / 5 k-steps: shorter than a k-split
+])
+def test_wide_pass_shapes_bf16(shape):
+    """A batch of 5 sequences with 190 tree nodes in all, i.e. one wide pass (tiled GEMM, band-block
+    finishing kernels, direct or merged attention output), over head sizes, GQA groupings and widths
+    that leave partial feature tiles, partial row tiles and odd k-step counts: every sequence equals
+    the oracle run on it alone; then the same model prefills 150 positions in a wide pass."""
+    from paper_2507_18181_amd import binding as B
+    cfg = dict(wl.MODELS["tiny"], **shape)
+    w = wl.make_weights(cfg, 141, "bf16")
+    rng = np.random.default_rng(142)
+    sizes, Ls = (64, 7, 33, 64, 22), [150, 0, 31, 64, 97]
+    nb, cap = len(sizes), 224
+    K, V = wl.seeded_cache(cfg, 143, np.asarray(Ls, np.int32), cap, "bf16", batch=nb)
+    om = oracle.OracleModel(cfg, w)
+    ver = _verifier(cfg, w, "bf16", max_nodes=64, capacity=cap, max_batch=nb)
+    assert B.specasr_uses_mfma(ver.ctx, sum(sizes)) == 1
+    ver.set_cache(K, V, Ls)
+    trees = [wl.random_tree(rng, n, max_children=3) for n in sizes]
+    toks = [rng.integers(0, cfg["vocab"], n).astype(np.int32) for n in sizes]
+    fw = ver.tree_forward(toks, trees, want_logits=True)
+    assert fw["status"] == 0
+    k1, v1 = ver.get_cache()
+    for b in range(nb):
+        ref = om.tree_forward(np.ascontiguousarray(K[b]), np.ascontiguousarray(V[b]), Ls[b], toks[b], trees[b])
+        check_forward(ref, fw["logits"][b].cpu().numpy(), fw["argmax"][b].cpu().numpy(), TOL_BF16)
+        check_tree_kv(k1[b], v1[b], Ls[b], ref, TOL_BF16)
+    # prefill of sequence 1 (empty so far): 150 positions = one wide pass of 128 + 22 rows
+    text = rng.integers(0, cfg["vocab"], 150).astype(np.int32)
+    ver.set_cache(K, V, Ls)
+    out = ver.prefill([[], text, [], [], []])
+    assert out["status"] == 0 and ver.kv_len[1] == 150
+    kc, vc = K[1].copy(), V[1].copy()
+    Lp, last = om.prefill(kc, vc, 0, None, text, chunk=64)
+    k2, v2 = ver.get_cache()
+    for got, want in ((k2[1], kc), (v2[1], vc)):
+        g, wv = widen_cache(got[:, :, :Lp]), widen_cache(want[:, :, :Lp])
+        assert np.abs(g - wv).max() <= 5e-3 * np.abs(wv).max()
+    srt = np.sort(last)
+    if srt[-1] - srt[-2] > 0.05:
+        assert out["next_token"][1] == int(np.argmax(last))
+    ver.close()
+
+
+@pytest.mark.parametrize("shape", [
     dict(d_model=48, d_ffn=80, n_heads=1, n_kv_heads=1, head_dim=64, vocab=97),      # 3 k-steps: fewer than wavefronts
     dict(d_model=272, d_ffn=1008, n_heads=4, n_kv_heads=2, head_dim=64, vocab=1003),  # 17 / 63 k-steps, 31.5 FFN bands
     dict(d_model=1040, d_ffn=2064, n_heads=8, n_kv_heads=2, head_dim=128, vocab=515, n_layers=1),  # 65 / 129 k-steps
