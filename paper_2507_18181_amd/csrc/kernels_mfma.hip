@@ -245,25 +245,39 @@ hipError_t gemm_skinny_set_lds_limit() {
   return e;
 }
 
-// --------------------------------------------------------------------------- wide GEMM (prefill)
-// The same product for hundreds of activation rows (a prefill pass over many positions at once):
-// now every weight tile is used by all rows, the stage is bound by the matrix cores, and the
-// classical tiling applies.  One workgroup of 4 wavefronts computes 256 output features x 128
-// rows; per stage of 2 k-steps the 16 weight tiles and the 16 activation tiles (hi and lo plane)
-// are copied global -> registers -> LDS as they are (both sides are already in MFMA operand
-// order, so the copy is linear and every LDS access is a conflict-free 16 bytes per lane), double
-// buffered with one barrier per stage.  A wavefront owns 128 features x 64 rows: 4 weight tiles
-// and 2 x 2 activation tiles from LDS feed 16 MFMAs per k-step into 8 accumulator tiles.  Two
-// workgroups fit a compute unit (64 KB LDS, < 256 registers), so one's barrier and LDS phases
-// hide under the other's MFMAs.  Workgroups that share a weight tile (the row tiles of one
-// feature tile) get consecutive slots of one XCD and meet in its L2.
+// --------------------------------------------------------------------------- wide GEMM (prefill, large batches)
+// The same product for hundreds of activation rows (a prefill pass over many positions at once,
+// or the trees of a large batch): now every weight tile is used by all rows, the stage is bound
+// by the matrix cores, and the classical tiling applies.  One workgroup of 4 wavefronts computes
+// 256 output features x 128 rows.  Both operands already are in MFMA operand order in memory, one
+// 1 KB tile per (band or row group, k-step), so a tile is copied with ONE direct-to-LDS load per
+// wavefront (global_load_lds_dwordx4: lane l's 16 bytes land at base + 16 l -- no staging
+// registers, no LDS store instructions) and read back with conflict-free 16-byte LDS loads.
+// LDS holds a ring of 4 stages of one k-step each (8 weight tiles + 2 planes x 4 activation
+// tiles = 16 KB); the copies run 3 k-steps ahead of the MFMAs.  Per k-step: wait until this
+// wavefront's copies of the current stage have landed (vmcnt: the 8 copies of the two younger
+// stages may stay in flight) and its own LDS reads of the previous stage have returned, barrier
+// (now every wavefront's part of the current stage is there, and nobody reads the previous stage
+// any more), start the copies of k-step +3 into the previous stage's buffer, multiply.  A
+// wavefront owns 128 features x 64 rows: 4 + 2 x 2 operand tiles feed 16 MFMAs per k-step into 8
+// accumulator tiles (hi products first, then lo: 8 independent accumulators between two uses of
+// one).  The barrier is the bare s_barrier: __syncthreads would add a fence that waits for ALL
+// copies in flight.  Copies past the end of the k range are clamped to valid tiles and multiplied
+// by zero, so the number of copies in flight is the same in every iteration; before a wavefront
+// leaves the loop it waits for all of them (the LDS may be handed to another workgroup).
+// 64 KB LDS and < 256 registers let two workgroups share a compute unit.  Workgroups that share
+// a weight tile (the row tiles of one feature tile) get consecutive slots of one XCD.
 //   part[s][band][row][o % 32] as for the skinny kernel; nb = row groups of 32 in Xp, a multiple
 //   of 4 (the buffer is allocated to that size; rows >= `rows` hold anything and are not stored).
 // grid.x = 8 * (nb / 4) * ceil(ceil(n_bands / 8) / 8) * S, block 256.
-constexpr int kWideKB = 2;          // k-steps per LDS stage
 constexpr int kWideTileBands = 8;   // 256 output features per workgroup
 constexpr int kWideTileGroups = 4;  // 128 rows per workgroup
-constexpr int kWideStageVecs = (kWideTileBands + 2 * kWideTileGroups) * kWideKB * 64;  // 16-byte vectors per stage
+constexpr int kWideStageTiles = kWideTileBands + 2 * kWideTileGroups;  // 1 KB tiles per stage (one k-step)
+
+__device__ __forceinline__ void copy_tile_to_lds(const u32x4 *src_lane, u32x4 *dst_tile) {
+  __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)src_lane,
+                                   (void __attribute__((address_space(3))) *)dst_tile, 16, 0, 0);
+}
 
 template <int STAGE>
 __global__ __launch_bounds__(256, 2) void gemm_wide_kernel(const u32x4 *__restrict__ Wp,
@@ -271,7 +285,8 @@ __global__ __launch_bounds__(256, 2) void gemm_wide_kernel(const u32x4 *__restri
                                                            float *__restrict__ part, int rows,
                                                            int rows_pad, int n_bands, int ksteps,
                                                            int nb, int S) {
-  __shared__ u32x4 lds[2 * kWideStageVecs];
+  // four separate arrays: the compiler can tell a copy into one from the reads of another
+  __shared__ u32x4 s0[kWideStageTiles * 64], s1[kWideStageTiles * 64], s2[kWideStageTiles * 64], s3[kWideStageTiles * 64];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int n_mt = nb / kWideTileGroups, n_nt = (n_bands + kWideTileBands - 1) / kWideTileBands, n_nt8 = (n_nt + 7) / 8;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -281,29 +296,27 @@ __global__ __launch_bounds__(256, 2) void gemm_wide_kernel(const u32x4 *__restri
   const int k0 = (int)((int64_t)ksteps * s / S), k1 = (int)((int64_t)ksteps * (s + 1) / S);
   const int wn = wave & 1, wm = wave >> 1;
   const int64_t x_plane = (int64_t)ksteps * nb * 64;
-
-  // global -> registers: 4 weight tiles and 4 activation tiles per wavefront and stage (tiles past
-  // the matrix edge are clamped to valid ones; their products are never stored or never issued)
-  u32x4 stA[4], stB[4];
-  auto fetch = [&](int kt) {
+  // the 4 tiles this wavefront copies per stage: wavefronts 0, 1 the weight bands 4w .. 4w+3 (bands
+  // past the matrix edge are clamped to the last one; their products are never stored), wavefronts
+  // 2, 3 the activation tiles [plane][row group]
+  const u32x4 *src[4];
+  int64_t kstride[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int ti = wave * 4 + i;
-      const int band = min(nt * kWideTileBands + (ti >> 1), n_bands - 1), ks = min(kt + (ti & 1), ksteps - 1);
-      stA[i] = load_stream(Wp + ((int64_t)band * ksteps + ks) * 64 + lane);
+  for (int i = 0; i < 4; ++i) {
+    const int ti = wave * 4 + i;
+    if (ti < kWideTileBands) {
+      src[i] = Wp + (int64_t)min(nt * kWideTileBands + ti, n_bands - 1) * ksteps * 64 + lane;
+      kstride[i] = 64;
+    } else {
+      const int tb = ti - kWideTileBands;
+      src[i] = Xp + (tb >> 2) * x_plane + (int64_t)(mt * kWideTileGroups + (tb & 3)) * 64 + lane;
+      kstride[i] = (int64_t)nb * 64;
     }
+  }
+  auto issue = [&](u32x4 *buf, int kt) {
+    const int ks = min(kt, ksteps - 1);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int ti = wave * 4 + i;
-      const int pl = ti >> 3, ks = min(kt + ((ti >> 2) & 1), ksteps - 1), grp = mt * kWideTileGroups + (ti & 3);
-      stB[i] = Xp[pl * x_plane + ((int64_t)ks * nb + grp) * 64 + lane];
-    }
-  };
-  auto stash = [&](u32x4 *buf) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) buf[(wave * 4 + i) * 64 + lane] = stA[i];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) buf[(kWideTileBands * kWideKB + wave * 4 + i) * 64 + lane] = stB[i];
+    for (int i = 0; i < 4; ++i) copy_tile_to_lds(src[i] + ks * kstride[i], buf + (wave * 4 + i) * 64);
   };
   f32x16 acc[4][2];
 #pragma unroll
@@ -312,43 +325,45 @@ __global__ __launch_bounds__(256, 2) void gemm_wide_kernel(const u32x4 *__restri
     for (int g = 0; g < 2; ++g)
 #pragma unroll
       for (int j = 0; j < 16; ++j) acc[i][g][j] = 0.f;
-  auto compute = [&](const u32x4 *buf, int kt) {
-    const u32x4 *sA = buf, *sB = buf + kWideTileBands * kWideKB * 64;
+  auto compute = [&](const u32x4 *buf, bool live) {
+    const u32x4 z = (u32x4){0u, 0u, 0u, 0u};
+    bf16x8 a[4], bh[2], bl[2];
 #pragma unroll
-    for (int ks = 0; ks < kWideKB; ++ks) {
-      if (kt + ks < k1) {
-        bf16x8 a[4], bh[2], bl[2];
+    for (int i = 0; i < 4; ++i) a[i] = __builtin_bit_cast(bf16x8, buf[(4 * wn + i) * 64 + lane]);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) a[i] = __builtin_bit_cast(bf16x8, sA[((4 * wn + i) * kWideKB + ks) * 64 + lane]);
-#pragma unroll
-        for (int g = 0; g < 2; ++g) {
-          bh[g] = __builtin_bit_cast(bf16x8, sB[((0 * kWideKB + ks) * 4 + 2 * wm + g) * 64 + lane]);
-          bl[g] = __builtin_bit_cast(bf16x8, sB[((1 * kWideKB + ks) * 4 + 2 * wm + g) * 64 + lane]);
-        }
-        // all hi products, then all lo products: 8 independent accumulators between two uses of one
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int g = 0; g < 2; ++g) acc[i][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bh[g], acc[i][g], 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int g = 0; g < 2; ++g) acc[i][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bl[g], acc[i][g], 0, 0, 0);
-      }
+    for (int g = 0; g < 2; ++g) {
+      bh[g] = __builtin_bit_cast(bf16x8, live ? buf[(kWideTileBands + 2 * wm + g) * 64 + lane] : z);
+      bl[g] = __builtin_bit_cast(bf16x8, live ? buf[(kWideTileBands + kWideTileGroups + 2 * wm + g) * 64 + lane] : z);
     }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int g = 0; g < 2; ++g) acc[i][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bh[g], acc[i][g], 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int g = 0; g < 2; ++g) acc[i][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bl[g], acc[i][g], 0, 0, 0);
   };
-  fetch(k0);
-  stash(lds);
-  __syncthreads();
-  int cur = 0;
-  for (int kt = k0; kt < k1; kt += kWideKB) {
-    const bool more = kt + kWideKB < k1;
-    if (more) fetch(kt + kWideKB);  // in flight while this stage is multiplied
-    compute(lds + cur * kWideStageVecs, kt);
-    if (more) stash(lds + (cur ^ 1) * kWideStageVecs);  // last read before the previous barrier
-    __syncthreads();
-    cur ^= 1;
+  // s_waitcnt immediate of gfx9-class parts: vmcnt in bits 3:0 (and 15:14), expcnt 6:4, lgkmcnt 11:8
+  constexpr int kWaitCopies8Lds0 = 0x0078;  // vmcnt(8) lgkmcnt(0), expcnt untouched (7)
+  constexpr int kWaitCopies0 = 0x0F70;      // vmcnt(0)
+  auto step = [&](const u32x4 *cur, u32x4 *prev, int kt) {
+    __builtin_amdgcn_s_waitcnt(kWaitCopies8Lds0);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");  // no LDS access of this step may be scheduled above the barrier
+    issue(prev, kt + 3);
+    compute(cur, kt < k1);
+  };
+  issue(s0, k0);
+  issue(s1, k0 + 1);
+  issue(s2, k0 + 2);
+  for (int kt = k0; kt < k1; kt += 4) {
+    step(s0, s3, kt);
+    step(s1, s0, kt + 1);
+    step(s2, s1, kt + 2);
+    step(s3, s2, kt + 3);
   }
+  __builtin_amdgcn_s_waitcnt(kWaitCopies0);
   // C layout: register j of lane l = row l%32 of the group, output feature 8*(j/4) + 4*(l/32) + j%4
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -370,13 +385,14 @@ __global__ __launch_bounds__(256, 2) void gemm_wide_kernel(const u32x4 *__restri
 int wide_row_groups(int rows) { return (rows + 32 * kWideTileGroups - 1) / (32 * kWideTileGroups) * kWideTileGroups; }
 
 // k-split S of a wide GEMM (any integer, each split >= 8 k-steps), from a cost model fitted to
-// measurements on MI355X, in microseconds: the workgroups spread round-robin over the compute
-// units, which work them off two at a time; a workgroup costs 4 us of prologue and epilogue plus
-// 0.45 us of its compute unit per k-step, 0.53 when it runs there alone (an odd one left over at
-// the end, or fewer workgroups than compute units); every split writes the output once as fp32
-// partial sums that the consumer reads again (0.3 us per MB).  E.g. gate|up of the 1.1B model at
-// 384 rows has 132 tiles: S = 3 fills the 512 workgroup slots in one go (4.54 ms per call),
-// S = 4 needs a second, almost empty round (4.97 ms).
+// measurements on MI355X (7B shapes at 256 and 512 rows), in microseconds.  One workgroup keeps
+// the matrix cores of its compute unit almost busy by itself, so a compute unit works its
+// workgroups off one after the other in effect: 18 us for launch, pipeline fill and the last
+// epilogue, 0.33 us per k-step (0.28 while fewer workgroups than compute units run), 6 us per
+// further workgroup on the same compute unit, and every split writes the output once as fp32
+// partial sums that the consumer reads again (0.3 us per MB).  What this mostly decides is how
+// many rounds of workgroups a launch takes: gate|up at 512 rows of the 7B model has 344 tiles on
+// 256 compute units: S = 1 187 us, S = 2 162 us, S = 4 183 us.
 int wide_gemm_splits(int n_bands, int ksteps, int rows, int n_cu) {
   const int64_t tiles = (int64_t)((n_bands + kWideTileBands - 1) / kWideTileBands) * (wide_row_groups(rows) / kWideTileGroups);
   const double out_mb = (double)n_bands * 32 * part_rows_pad(rows) * 4 / 1e6;
@@ -384,9 +400,8 @@ int wide_gemm_splits(int n_bands, int ksteps, int rows, int n_cu) {
   double best_cost = 1e300;
   for (int S = 1; S <= 16 && ksteps / S >= 8; ++S) {
     const int64_t wgs = tiles * S, per_cu = (wgs + n_cu - 1) / n_cu;
-    const double len = (double)ksteps / S;
-    const double pairs = wgs <= n_cu ? 0.0 : (double)(per_cu / 2), alone = wgs <= n_cu ? 1.0 : (double)(per_cu % 2);
-    const double cost = pairs * 2.0 * (len * 0.45 + 4.0) + alone * (len * 0.53 + 4.0) + S * out_mb * 0.3;
+    const double len = (double)ksteps / S, tk = wgs >= n_cu ? 0.33 : 0.28;
+    const double cost = 18.0 + per_cu * len * tk + (per_cu - 1) * 6.0 + S * out_mb * 0.3;
     if (cost < best_cost) { best_cost = cost; best = S; }
   }
   return best;
