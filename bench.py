@@ -141,6 +141,93 @@ def bench_prefill(args, spec, cfg, w_host, ver, stage_id, t_gen, log):
     print(json.dumps(result), flush=True)
 
 
+def bench_batch(args, spec, cfg, w_host, w_dev, t_gen, log):
+    """Times specasr_verify_tree on a batch workload (config 4: 16 utterances with prefixes of
+    200..1500 positions, a 24-node sparse tree each): one call verifies every utterance's tree."""
+    import numpy as np
+    import torch
+    import workload as wl
+    from paper_2507_18181_amd import binding as B
+    from paper_2507_18181_amd.runtime import Verifier
+    Bn = spec["batch"]
+    rng = np.random.default_rng([spec["seed"], 1])
+    Ls = rng.integers(spec["prefix_range"][0], spec["prefix_range"][1] + 1, Bn).astype(np.int32)
+    cap = int(Ls.max()) + 64
+    ver = Verifier(cfg, w_dev, "bf16", max_nodes=64, capacity=cap, max_batch=Bn, weights_on_device=True)
+    K, V = wl.seeded_cache(cfg, spec["seed"], Ls, cap, "bf16", batch=Bn)
+    ver.set_cache(K, V, Ls)
+    t = spec["tree"]
+    trees, toks = [], []
+    for b in range(Bn):
+        p, _, _ = wl.sparse_tree(rng, t["trunk"], t["n_branches"], t["branch_depth"], t["rule"])
+        trees.append(p)
+        toks.append(wl.tree_tokens(rng, p, cfg["vocab"]))
+    rows = sum(len(p) for p in trees)
+    stage_id = ["qkv", "o", "gate_up", "down", "lm_head"].index(args.stage)
+
+    def step():
+        ver.kv_len[:] = Ls
+        out = ver.verify_tree(toks, trees)
+        assert out["status"] == 0
+        return out
+
+    log("batch warm-up")
+    for _ in range(args.warmup):
+        step()
+    wide = rows >= 129
+    assert B.specasr_profile_stage(ver.ctx, stage_id, 2 if wide else 1) == 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    rc, stage_ms, stage_launches, stage_bytes = B.specasr_stage_time(ver.ctx)
+    rc2, stage_rows = B.specasr_stage_rows(ver.ctx)
+    B.specasr_profile_stage(ver.ctx, stage_id, False)
+    kern_ms = stage_ms / max(1, stage_launches)
+    if wide:
+        flops = 2.0 * (stage_rows / max(1, stage_launches)) * (stage_bytes / 2.0)
+        tf = flops / (kern_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "gemm_wide_kernel (%s projection, %d rows)" % (args.stage, rows),
+                    "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                    "launches_timed": stage_launches, "avg_launch_us": round(kern_ms * 1e3, 2),
+                    "flops_per_launch": flops, "mfma_flops_issued_per_launch": 2.0 * flops}
+    else:
+        gbs = stage_bytes / (kern_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "gemm_skinny_kernel (%s projection)" % args.stage,
+                    "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "launches_timed": stage_launches,
+                    "avg_launch_us": round(kern_ms * 1e3, 2), "bytes_per_launch": stage_bytes}
+    result = {
+        "metric": "tree_verify_steps_per_s", "value": round(Bn * args.steps / dt, 2), "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "model": spec["model"], "batch": Bn, "tree_nodes_total": rows,
+                   "kv_prefix_min": int(Ls.min()), "kv_prefix_max": int(Ls.max())},
+        "calls_per_s": round(args.steps / dt, 2),
+        "note": "value = utterance verify steps per second (batch x calls/s); ms_per_step is per call",
+        "roofline": roofline, "weights_gen_s": round(t_gen, 1),
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        log("timing the CPU oracle on two of the utterances")
+        om = oracle.OracleModel(cfg, w_host)
+        t1 = time.perf_counter()
+        for b in (0, 1):
+            r = om.tree_forward(np.ascontiguousarray(K[b]), np.ascontiguousarray(V[b]), int(Ls[b]), toks[b], trees[b],
+                                want_logits=False)
+            oracle.accept(toks[b], trees[b], r["amax"])
+        spent = time.perf_counter() - t1
+        result["cpu_baseline"] = {
+            "value": round(2 / spent, 4), "unit": "steps/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "fp64 oracle, whole verify step of 2 of the %d utterances one after the other = %.1f s "
+                      "of CPU work" % (Bn, spent)}
+    print(json.dumps(result), flush=True)
+    ver.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -172,13 +259,21 @@ def main():
     spec = wl.WORKLOADS[args.workload]
     cfg = wl.MODELS[spec["model"]]
     dtype = spec["dtype"]
+
+    def log(msg):
+        print("[bench] " + msg, file=sys.stderr, flush=True)
+
+    if "batch" in spec:                                    # several utterances per call
+        log("generating %s weights on the host" % spec["model"])
+        t0 = time.perf_counter()
+        w_host = wl.make_weights(cfg, spec["seed"], dtype, threads=16)
+        t_gen = time.perf_counter() - t0
+        bench_batch(args, spec, cfg, w_host, upload_weights(w_host, "cuda:0"), t_gen, log)
+        return
     kv_len = spec["n_audio"] + spec["n_text"]
     parents, tokens = wl.make_tree(args.workload)
     n = len(parents)
     capacity = kv_len + 64
-
-    def log(msg):
-        print("[bench] " + msg, file=sys.stderr, flush=True)
 
     log("generating %s weights on the host" % spec["model"])
     t0 = time.perf_counter()

@@ -175,7 +175,7 @@ def test_draft_1b_two_branch_recycling_tree(model_1b):
 def test_cfg4_1b_batch16_ragged(model_1b):
     """16 utterances, prefix lengths uniform in [200, 1500], each with its own 24-node tree (trunk 16 +
     two depth-4 branches): one call; every sequence equals the oracle run on it alone.  384 rows in
-    total: the library runs them as eight groups of two sequences on the MFMA kernels."""
+    total: the library runs them as one wide pass (tiled GEMM, band-block finishing kernels)."""
     from paper_2507_18181_amd import binding as B
     spec = wl.WORKLOADS["cfg4_1b_b16"]
     cfg = model_1b.cfg
