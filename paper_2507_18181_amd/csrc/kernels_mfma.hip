@@ -390,7 +390,7 @@ int wide_row_groups(int rows) { return (rows + 32 * kWideTileGroups - 1) / (32 *
 // workgroups off one after the other in effect: 18 us for launch, pipeline fill and the last
 // epilogue, 0.33 us per k-step (0.28 while fewer workgroups than compute units run), 6 us per
 // further workgroup on the same compute unit, and every split writes the output once as fp32
-// partial sums that the consumer reads again (0.3 us per MB).  What this mostly decides is how
+// partial sums that the consumer reads again (0.3 us per MB + 0.5 us per split).  What this mostly decides is how
 // many rounds of workgroups a launch takes: gate|up at 512 rows of the 7B model has 344 tiles on
 // 256 compute units: S = 1 187 us, S = 2 162 us, S = 4 183 us.
 int wide_gemm_splits(int n_bands, int ksteps, int rows, int n_cu) {
@@ -401,7 +401,7 @@ int wide_gemm_splits(int n_bands, int ksteps, int rows, int n_cu) {
   for (int S = 1; S <= 16 && ksteps / S >= 8; ++S) {
     const int64_t wgs = tiles * S, per_cu = (wgs + n_cu - 1) / n_cu;
     const double len = (double)ksteps / S, tk = wgs >= n_cu ? 0.33 : 0.28;
-    const double cost = 18.0 + per_cu * len * tk + (per_cu - 1) * 6.0 + S * out_mb * 0.3;
+    const double cost = 18.0 + per_cu * len * tk + (per_cu - 1) * 6.0 + S * (out_mb * 0.3 + 0.5);
     if (cost < best_cost) { best_cost = cost; best = S; }
   }
   return best;
