@@ -229,9 +229,9 @@ specasr_status specasr_commit(specasr_ctx *ctx, specasr_kv *kv, const int32_t *n
                               size_t workspace_bytes, void *stream);
 
 /* Which kernels a forward over `rows` tree nodes in total would use: 1 = the bf16 MFMA path
- * (a call with 65..128 rows runs as consecutive groups of whole sequences with at most 64 rows
- * each, a larger one as a single pass with its projections on the tiled large-M GEMM), 0 = the
- * dtype-generic kernels (fp32 models, SPECASR_FLAG_GENERIC_KERNELS /
+ * (a call with more than 64 rows runs as a single pass with its projections on the tiled
+ * large-M GEMM; where the head size has no MFMA attention, as consecutive groups of whole
+ * sequences with at most 64 rows each), 0 = the dtype-generic kernels (fp32 models, SPECASR_FLAG_GENERIC_KERNELS /
  * NO_REPACK, shapes the MFMA tiling does not cover). */
 int32_t specasr_uses_mfma(const specasr_ctx *ctx, int32_t rows);
 

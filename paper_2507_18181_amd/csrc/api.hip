@@ -680,11 +680,12 @@ struct SeqGroup {
 // The MFMA kernels take at most 64 activation rows, so a call with more tree nodes in total is
 // run as consecutive groups of whole sequences with <= 64 rows each (a tree has <= 64 nodes);
 // the dtype-generic kernels take the whole call at once.
-// From kWideMinRows rows on (tuning aid: SPECASR_WIDE_MIN_ROWS) the whole call is ONE group on the
-// wide kernels instead: the weights are streamed once, not once per group.
+// Where the context has the wide buffers, a call with more than 64 rows is ONE group on the wide
+// kernels instead: the weights are streamed once, not once per group (7B, 2 x 64 nodes: 6.8 ms
+// against 8.5 in two groups; tuning aid: SPECASR_WIDE_MIN_ROWS raises the threshold).
 int wide_min_rows() {
   const char *e = getenv("SPECASR_WIDE_MIN_ROWS");
-  const int x = e ? atoi(e) : 129;
+  const int x = e ? atoi(e) : 65;
   return x < 65 ? 65 : x;
 }
 

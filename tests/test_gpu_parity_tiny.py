@@ -176,18 +176,23 @@ def test_batch_of_ragged_sequences():
     ver.close()
 
 
-@pytest.mark.parametrize("sizes", [
-    (20, 30, 14, 40, 1, 5, 16),      # 126 rows: consecutive groups of whole sequences, <= 64 rows each
-    (20, 30, 14, 64, 1, 5, 16),      # 150 rows: one pass on the wide (tiled GEMM) kernels, 2 row tiles
-    (64, 64, 64, 64, 3, 64, 64),     # 387 rows: wide, 4 row tiles, the last almost empty
+@pytest.mark.parametrize("sizes,min_wide_rows", [
+    ((20, 30, 14, 40, 1, 5, 16), "100000"),  # 126 rows, wide passes off: groups of whole sequences, <= 64 rows each
+    ((20, 30, 14, 64, 1, 5, 16), "100000"),  # 150 rows in groups, one of them a full 64-node tree
+    ((20, 30, 14, 1, 1, 5, 16), None),       # 87 rows: one pass on the wide (tiled GEMM) kernels, one row tile
+    ((20, 30, 14, 64, 1, 5, 16), None),      # 150 rows: wide, 2 row tiles
+    ((64, 64, 64, 64, 3, 64, 64), None),     # 387 rows: wide, 4 row tiles, the last almost empty
 ])
-def test_batch_above_64_rows_runs_on_the_mfma_path(sizes):
-    """Seven bf16 sequences with more than 64 tree nodes in total.  Up to 128 rows the call is
-    processed as consecutive groups of whole sequences with at most 64 rows each on the skinny
-    kernels; from 129 rows on as one pass whose projections run on the tiled GEMM.  Either way
-    every sequence equals the oracle run on it alone, tree_forward agrees with verify_tree, and
-    the draft-side read-out equals the oracle's read-out of the same logits."""
+def test_batch_above_64_rows_runs_on_the_mfma_path(sizes, min_wide_rows, monkeypatch):
+    """Seven bf16 sequences with more than 64 tree nodes in total: one pass whose projections run
+    on the tiled GEMM -- or, where wide passes are not available (here: switched off through the
+    tuning variable), consecutive groups of whole sequences with at most 64 rows each on the skinny
+    kernels, spread over several streams.  Either way every sequence equals the oracle run on it
+    alone, tree_forward agrees with verify_tree, and the draft-side read-out equals the oracle's
+    read-out of the same logits."""
     from paper_2507_18181_amd import binding as B
+    if min_wide_rows is not None:
+        monkeypatch.setenv("SPECASR_WIDE_MIN_ROWS", min_wide_rows)
     cfg = wl.MODELS["tiny"]
     w = wl.make_weights(cfg, 91, "bf16")
     rng = np.random.default_rng(92)
