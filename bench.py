@@ -84,7 +84,7 @@ def bench_prefill(args, spec, cfg, w_host, ver, stage_id, t_gen, log):
     log("prefill warm-up")
     for _ in range(warm):
         step()
-    wide = B.specasr_uses_mfma(ver.ctx, 64) == 1 and T > 3 * 64
+    wide = B.specasr_uses_mfma(ver.ctx, 64) == 1 and T > 64
     assert B.specasr_profile_stage(ver.ctx, stage_id, 2 if wide else 1) == 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -121,7 +121,7 @@ def bench_prefill(args, spec, cfg, w_host, ver, stage_id, t_gen, log):
         "data": "synthetic",
         "config": {"workload": args.workload + " (prefix prefill)", "model": spec["model"],
                    "audio_positions": n_a, "prompt_tokens": n_t, "chunk": 64,
-                   "wide_pass_rows": 512 if wide else 0, "batch": 1},
+                   "wide_pass_rows": min(T, 1024) if wide else 0, "batch": 1},
         "roofline": roofline,
         "weights_gen_s": round(t_gen, 1),
     }

@@ -138,7 +138,7 @@ void specasr_destroy(specasr_ctx *ctx);
 /* Bytes of device workspace a call with `batch` sequences needs (256-byte aligned
  * base required).  Depends on the model, max_nodes and batch only.  On the bf16 MFMA path it
  * covers one set of buffers per internal stream plus one set for passes over up to
- * max(8, batch) x max_nodes rows (prefill, large batches). */
+ * max(16, batch) x max_nodes rows (prefill, large batches). */
 size_t specasr_workspace_bytes(const specasr_ctx *ctx, int32_t batch);
 
 /* One whole verification round (Sec. II-B, Sec. IV-C): tree forward, per-node
@@ -181,10 +181,11 @@ specasr_status specasr_tree_forward_top2(specasr_ctx *ctx, specasr_kv *kv, const
  * every sequence b: position i takes the embedding row input_embeds[b][i] where use_embed[b][i] is
  * non-zero, the token embedding of tokens[b][i] otherwise.  The positions are run through the
  * decoder in chain-shaped chunks of at most max_nodes rows (a chain is the tree whose mask is the
- * causal one) -- on the bf16 MFMA path up to 8 consecutive chunks of a sequence at once, as one
- * pass over up to 8 x max_nodes rows whose projections are matrix-core-bound GEMMs -- their K/V
- * rows land in slots kv_len .. kv_len + n_pos - 1, and kv_len advances by n_pos.  The LM head runs
- * only for the last chunk, and only if next_token is given.
+ * causal one) -- on the bf16 MFMA path a sequence that adds more than max_nodes positions takes
+ * up to 16 consecutive chunks at once, as one pass over up to 16 x max_nodes rows whose projections
+ * are matrix-core-bound GEMMs -- their K/V rows land in slots kv_len .. kv_len + n_pos - 1, and
+ * kv_len advances by n_pos.  The LM head runs only for the last chunk, and only if next_token is
+ * given.
  *   tokens        HOST int32 [batch][max_pos], may be NULL if every position is an embedding
  *   input_embeds  DEVICE [batch][max_pos][d_model] in config.dtype, with use_embed HOST uint8
  *                 [batch][max_pos]; both NULL when every position is a token

@@ -187,7 +187,7 @@ WsLayout ws_layout(const specasr_ctx *ctx, int batch) {
 // A wide prefill pass takes up to kWideSeqs pieces of max_nodes consecutive positions of ONE
 // sequence at once (each piece is a chain "tree" with its own kv_len on the shared cache), so
 // that the projections become GEMMs over hundreds of rows.  Its buffers follow the lanes'.
-constexpr int kWideSeqs = 8;
+constexpr int kWideSeqs = 16;
 
 inline int wide_seqs(int batch) { return batch > kWideSeqs ? batch : kWideSeqs; }
 
@@ -1059,14 +1059,13 @@ specasr_status specasr_prefill(specasr_ctx *ctx, specasr_kv *kv, const int32_t *
   std::vector<int32_t> chunk_tok(c.max_nodes), chain(c.max_nodes);
   for (int i = 0; i < c.max_nodes; ++i) chain[i] = i - 1;
   std::vector<int32_t> kv_len_now(kv->kv_len, kv->kv_len + B);
-  // Work list.  Where the context has the wide buffers, the part of a sequence in front of its last
-  // chunk is taken in passes of up to kWideSeqs pieces of max_nodes positions (projections as
-  // matrix-core-bound GEMMs over hundreds of rows).  The last chunk joins the last pass when it
-  // fits into that pass's last 128-row tile (it then costs no tile of its own; the pass reads out
-  // the token after the last position from its last piece only); otherwise it is a chunk of its
-  // own on the skinny kernels, which is cheaper than one more row tile through every GEMM
-  // (measured on the 7B prefix of 810 positions: 34.5 against 35.3 ms).  Contexts without wide
-  // buffers take every chunk on the skinny kernels.
+  // Work list.  Where the context has the wide buffers, a sequence that adds more than one chunk
+  // is taken in passes of up to kWideSeqs pieces of max_nodes positions (projections as
+  // matrix-core-bound GEMMs over hundreds of rows); the pass that holds the last position reads out
+  // the token after it from its last piece only.  One more 128-row tile through every GEMM costs
+  // less than a chunk of its own on the skinny kernels, which stream every weight once more
+  // (measured on the 7B prefix of 810 positions: 24.9 against 27.8 ms).  Contexts without wide
+  // buffers, and sequences that add a single chunk, take chunks on the skinny kernels.
   struct Item { int b, c0, n; bool wide; };
   std::vector<Item> items;
   const WsLayout LW = ws_layout_wide(ctx, B);
@@ -1074,10 +1073,8 @@ specasr_status specasr_prefill(specasr_ctx *ctx, specasr_kv *kv, const int32_t *
   for (int b = 0; b < B; ++b) {
     int c0 = 0;
     if (LW.total > 0 && n_pos[b] > 0) {
-      const int n_last = (n_pos[b] - 1) % c.max_nodes + 1, head = n_pos[b] - n_last;
-      const bool join = head % 128 != 0 && head % 128 + n_last <= 128;
-      const int wide_total = join ? n_pos[b] : head;
-      while (wide_total >= 2 * c.max_nodes && c0 < wide_total) {
+      const int wide_total = n_pos[b] > c.max_nodes ? n_pos[b] : 0;
+      while (c0 < wide_total) {
         const int n = std::min(wide_total - c0, kWideSeqs * c.max_nodes);
         items.push_back({b, c0, n, true});
         any_wide = true;

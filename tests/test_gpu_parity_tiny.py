@@ -478,13 +478,13 @@ def test_prefill_entry_point_equals_oracle_prefill(dtype, tol, max_nodes):
 
 
 @pytest.mark.parametrize("max_nodes,n_audio,n_text", [
-    (16, [250, 100, 64], [63, 15, 16]),     # 19 pieces + 9: passes of 128, 128, 48 rows; 7 pieces (112 rows); 4 pieces (64 rows)
-    (64, [150, 0, 140], [52, 0, 10]),       # 3 pieces (192 rows, half a row tile empty); nothing; 2 pieces (128 rows)
-    (24, [300, 20, 0], [0, 0, 49]),         # 12 pieces: 192 + 96 rows, embeddings only; one chunk; tokens only
+    (16, [250, 100, 64], [63, 15, 16]),     # 313 positions: passes of 256 and 57 rows; 115 rows (8 pieces, last of 3); 80 rows
+    (64, [150, 0, 140], [52, 0, 10]),       # 202 rows (4 pieces, last of 10; half a row tile empty); nothing; 150 rows
+    (24, [300, 20, 0], [0, 0, 49]),         # 300 rows (13 pieces), embeddings only; one chunk on the skinny kernels; 49 rows in 3 pieces, tokens only
 ])
 def test_prefill_wide_passes_equal_oracle_prefill(max_nodes, n_audio, n_text):
-    """Long prefixes: the library takes everything in front of the last chunk of a sequence in
-    passes of up to 8 chunks at once, whose projections run on the tiled (matrix-core-bound) GEMM
+    """Long prefixes: the library takes a sequence that adds more than one chunk in passes of up
+    to 16 chunks at once, whose projections run on the tiled (matrix-core-bound) GEMM
     -- row counts that fill, half fill and overflow its 128-row tiles, feature counts that leave a
     partial 256-feature tile (gate|up has 44 bands) and an odd number of k-steps (down: 43).  The
     result is the same as the oracle's position-by-chunk prefill."""
