@@ -73,7 +73,9 @@ __global__ __launch_bounds__(256) void tree_attention_kernel(StepMeta m, KvGeom 
   const int lane = threadIdx.x & 63, h = lane >> 5, ql = lane & 31;
   const int rgb = (blockIdx.x >> 3) % n_rgb, base = ((blockIdx.x >> 3) / n_rgb) * 8 + (blockIdx.x & 7);
   if (base >= n_chunks * Hkv) return;
-  const int chunk = base % n_chunks, kvh = base / n_chunks, seq = blockIdx.z;
+  // Sequences are dispatched last to first: the pieces of a prefill pass come in order of growing
+  // key count, and the workgroups with the longest key loops should start first.
+  const int chunk = base % n_chunks, kvh = base / n_chunks, seq = gridDim.z - 1 - blockIdx.z;
   const int G = H / Hkv;
   const int L = m.seq_kv_len(seq), n = m.seq_n_nodes(seq), r0 = m.seq_row_start(seq), rows = m.rows;
   const int T = L + n, QR = G * n;
