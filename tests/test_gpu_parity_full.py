@@ -9,7 +9,7 @@ import pytest
 
 import oracle
 import workload as wl
-from parity_util import (TOL_BF16, check_forward, check_tree_kv, top2_gap, GAP, widen_cache,
+from parity_util import (TOL_BF16, check_forward, check_tree_kv, top2_gap, GAP, widen_cache, row_rel_err,
                          check_top2, check_top2_against_oracle_forward)
 
 pytestmark = pytest.mark.gpu
@@ -229,6 +229,63 @@ def test_cfg3_7b_32_node_tree(model_7b):
     ver.set_cache(K, V, [L])
     _round_checks(ver, model_7b.om, tokens, parents, L)
     ver.close()
+
+
+def test_cfg3_7b_prefix_prefill_as_one_wide_pass(model_7b, monkeypatch):
+    """The 810-position prefix of config 3 (750 audio embeddings + 60 prompt tokens) through
+    specasr_prefill at the size bench.py --prefill times: ONE pass over 810 rows on the tiled GEMM
+    (7 row tiles of 128, the last one with 42 live rows; 13 chain pieces on the shared cache).
+    The oracle cannot prefill 32 layers of a 7B model in test time, so it is asked for what it can
+    compute: the K/V rows of layers 0 and 1 at the first 150 positions, which depend on nothing
+    behind them (a 2-layer model on the same weights, prefilled with those positions) -- layer 1
+    has the whole first layer of the pass in front of it (wide GEMMs, finishing kernels, causal
+    attention over two row tiles).  For all 32 layers and all positions the pass is compared with
+    the library's own chunk-by-chunk prefill on the skinny kernels (the path config 3's verify
+    parity covers), and the logits of one more token on top of either cache must agree."""
+    cfg, spec = model_7b.cfg, wl.WORKLOADS["cfg3_7b_n32"]
+    n_a, n_t = spec["n_audio"], spec["n_text"]
+    n = n_a + n_t
+    audio, text = wl.make_prefix_inputs(cfg, spec["seed"], n_a, n_t)
+    audio = wl.bf16_to_f32(wl.bf16_bits(audio.astype(np.float32)))
+    tok = np.zeros(n, np.int32)
+    tok[n_a:] = text
+    flags = [[1] * n_a + [0] * n_t]
+
+    def run():
+        ver = model_7b.verifier(n + 64)
+        emb = torch.zeros((1, n, cfg["d_model"]), dtype=torch.bfloat16, device=ver.device)
+        emb[0, :n_a] = torch.from_numpy(audio).to(ver.device).to(torch.bfloat16)
+        pf = ver.prefill([tok], embeds=emb, use_embed=flags)
+        assert pf["status"] == 0 and ver.kv_len[0] == n
+        k, v = ver.get_cache()
+        fw = ver.tree_forward([np.array([int(text[-1])], np.int32)], [np.array([-1], np.int32)])
+        assert fw["status"] == 0
+        lg = fw["logits"][0, :1].cpu().numpy().astype(np.float64)
+        ver.close()
+        return widen_cache(k[0, :, :, :n]), widen_cache(v[0, :, :, :n]), lg
+
+    kw, vw, lg_w = run()
+    P = 150
+    om2 = oracle.OracleModel(dict(cfg, n_layers=2), model_7b.w_host)
+    kc, vc = om2.empty_cache(P, np.uint16)
+    om2.prefill(kc, vc, 0, audio[:P].astype(np.float64), np.zeros(0, np.int32))
+    for got, want in ((kw, kc), (vw, vc)):
+        wv = widen_cache(want)
+        err = np.abs(got[:2, :, :P] - wv).max() / np.abs(wv).max()
+        print("layers 0-1, first %d positions: max err / max |value| = %.3e" % (P, err))
+        # rounded rows on both sides: one bf16 step (2^-8 of an element) plus the arithmetic difference
+        assert err <= 5e-3
+    monkeypatch.setenv("SPECASR_WIDE", "0")
+    kn, vn, lg_n = run()
+    for a, b in ((kw, kn), (vw, vn)):
+        err = np.abs(a - b).max(axis=(1, 2, 3)) / np.abs(b).max(axis=(1, 2, 3))     # per layer
+        print("wide pass vs chunks, per layer: max %.3e" % err.max())
+        assert err.max() <= TOL_BF16
+    err = row_rel_err(lg_w, lg_n)
+    print("next-token logits, wide vs chunked prefix: rel err %.3e" % err.max())
+    assert err.max() <= TOL_BF16
+    if top2_gap(lg_n)[0] > GAP:
+        assert np.argmax(lg_w[0]) == np.argmax(lg_n[0])
 
 
 def test_cfg6_13b_32_node_tree():
