@@ -481,6 +481,7 @@ def test_prefill_entry_point_equals_oracle_prefill(dtype, tol, max_nodes):
     (16, [250, 100, 64], [63, 15, 16]),     # 313 positions: passes of 256 and 57 rows; 115 rows (8 pieces, last of 3); 80 rows
     (64, [150, 0, 140], [52, 0, 10]),       # 202 rows (4 pieces, last of 10; half a row tile empty); nothing; 150 rows
     (24, [300, 20, 0], [0, 0, 49]),         # 300 rows (13 pieces), embeddings only; one chunk on the skinny kernels; 49 rows in 3 pieces, tokens only
+    (16, [200, 17, 0], [57, 0, 0]),         # 257 positions: a full pass of 256 rows and a pass of ONE row; 17 positions: pieces of 16 + 1; nothing
 ])
 def test_prefill_wide_passes_equal_oracle_prefill(max_nodes, n_audio, n_text):
     """Long prefixes: the library takes a sequence that adds more than one chunk in passes of up
