@@ -20,6 +20,9 @@
  *    only inside specasr_create (the optional repacked weight copy) and a few KB
  *    of pinned host staging memory on the first call that needs it.
  *  - `stream` is a raw hipStream_t (NULL = the default stream).
+ *  - A context is not thread-safe, and calls that use the same workspace must not overlap on
+ *    the device: issue them on one stream, or order them with events.  Calls on different
+ *    contexts (e.g. a draft and a target model) with their own workspaces are independent.
  *  - All validation happens on the host before anything is enqueued: a call that
  *    returns an error has not touched the cache, kv_len or any output.
  *  - Tree convention.  Node 0 of a tree is the last committed token whose K/V is
