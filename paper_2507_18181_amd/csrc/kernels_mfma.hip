@@ -713,9 +713,10 @@ __global__ __launch_bounds__(256) void swiglu_finish_kernel(const float *part, i
       make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
 }
 
-// The same for few rows (<= 64): one workgroup per (1024 features, row), one sum over the norm slabs
-// per wavefront -- with so few rows the band-block mapping above re-reads the slab sums too often
-// (7B, 32 rows: 5.5 against 6.8 us).
+// The same for one row group (<= 32 rows): one workgroup per (1024 features, row), one sum over the
+// norm slabs per wavefront -- with so few rows the band-block mapping above re-reads the slab sums
+// too often (7B, 32 rows: 5.5 against 6.8 us; from 33 rows on the band-block mapping wins: 7B, 64
+// rows 5.17 -> 5.11 ms per step).
 __global__ __launch_bounds__(256) void swiglu_finish_rows_kernel(const float *part, int n_splits, int rows,
                                                             int ldp, RowNorm nrm, int col_up, int F,
                                                             uint16_t *t, uint16_t *t_lo, int nb) {
@@ -749,7 +750,7 @@ __global__ __launch_bounds__(256) void swiglu_finish_rows_kernel(const float *pa
 
 void launch_swiglu_finish(const float *part, int n_splits, int rows, int ldp, const RowNorm &nrm,
                           int col_up, int F, uint16_t *t, uint16_t *t_lo, int nb, hipStream_t st) {
-  if (rows <= 64) {
+  if (rows <= 32) {
     dim3 grid((F / 4 + 255) / 256, rows);
     swiglu_finish_rows_kernel<<<grid, 256, 0, st>>>(part, n_splits, rows, ldp, nrm, col_up, F, t, t_lo, nb);
     return;
