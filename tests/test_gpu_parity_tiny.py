@@ -125,7 +125,7 @@ def test_random_trees_all_sizes(dtype, tol, flags):
     om, kc, vc, Lfull, _ = oracle_prefilled(cfg, w, audio, text, 420)
     ver = _verifier(cfg, w, dtype, max_nodes=64, capacity=420, flags=flags)
     for n, L in ((1, 0), (1, 5), (2, 64), (7, 63), (15, 255), (16, 256), (17, 257), (33, 100),
-                 (48, 340), (63, 129), (64, 340)):
+                 (48, 340), (63, 129), (64, 340), (64, 356)):   # the last: kv_len + n == capacity exactly
         parents = wl.random_tree(rng, n, max_children=3)
         tokens = rng.integers(0, cfg["vocab"], n).astype(np.int32)
         ver.set_cache(_store_cache(kc, dtype), _store_cache(vc, dtype), [L])
