@@ -222,6 +222,22 @@ specasr_status specasr_accept_from_logits(specasr_ctx *ctx, const specasr_tree *
                                           int32_t *accept_len_dev, int32_t *next_token_dev,
                                           void *workspace, size_t workspace_bytes, void *stream);
 
+/* specasr_accept_from_logits for callers that cannot allocate: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs, semantics and
+ * validation, but no workspace argument: the flattened tree metadata the kernels read lives in a
+ * device array of the library (40 KB, held by every GPU the library has run this call on until the
+ * process ends), filled by a kernel that receives each tree in its arguments.  The call allocates
+ * no device, pinned or host memory, copies nothing and does not synchronise; asynchronous on
+ * `stream`.  Limit: batch <= SPECASR_STATIC_MAX_BATCH (E_UNSUPPORTED beyond it, nothing enqueued).
+ * All calls on one GPU share the one array: calls that overlap on a GPU (other streams, other
+ * contexts, other threads) race; order them on one stream or with events. */
+#define SPECASR_STATIC_MAX_BATCH 16
+specasr_status specasr_accept_from_logits_static(specasr_ctx *ctx, const specasr_tree *tree,
+                                                 int32_t batch, const float *logits_dev,
+                                                 int32_t *argmax_dev, int32_t *path_dev,
+                                                 int32_t *accept_len_dev, int32_t *next_token_dev,
+                                                 void *stream);
+
 /* Stage: commit a path (the cache update that lets the next round start where
  * the accepted tokens end): for k < accept_len[b], cache slot kv_len+path[k] is
  * moved to slot kv_len+k for every layer and KV head, K and V, in place; then

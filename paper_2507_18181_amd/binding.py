@@ -27,10 +27,11 @@ SPECASR_F32, SPECASR_BF16 = 0, 1
 SPECASR_FLAG_GENERIC_KERNELS = 1
 SPECASR_FLAG_NO_REPACK = 2
 SPECASR_MAX_NODES = 64
+SPECASR_STATIC_MAX_BATCH = 16
 
 EXPORTS = ("specasr_create", "specasr_destroy", "specasr_workspace_bytes", "specasr_verify_tree",
            "specasr_tree_forward", "specasr_tree_forward_top2", "specasr_prefill", "specasr_accept",
-           "specasr_accept_from_logits",
+           "specasr_accept_from_logits", "specasr_accept_from_logits_static",
            "specasr_commit", "specasr_strerror", "specasr_last_hip_error", "specasr_abi_version",
            "specasr_uses_mfma", "specasr_profile_stage", "specasr_stage_time",
            "specasr_stage_rows")
@@ -111,6 +112,9 @@ def load_library(path=None):
     lib.specasr_accept_from_logits.restype = C.c_int
     lib.specasr_accept_from_logits.argtypes = [vp, C.POINTER(specasr_tree), C.c_int32, vp, vp, vp,
                                                vp, vp, vp, C.c_size_t, vp]
+    lib.specasr_accept_from_logits_static.restype = C.c_int
+    lib.specasr_accept_from_logits_static.argtypes = [vp, C.POINTER(specasr_tree), C.c_int32, vp, vp,
+                                                      vp, vp, vp, vp]
     lib.specasr_commit.restype = C.c_int
     lib.specasr_commit.argtypes = [vp, C.POINTER(specasr_kv), i32p, i32p, i32p, vp, C.c_size_t, vp]
     lib.specasr_strerror.restype = C.c_char_p
@@ -284,6 +288,14 @@ def specasr_accept_from_logits(ctx, tree, batch, logits_dev, argmax_dev, path_de
                                                      _ptr(accept_len_dev), _ptr(next_token_dev),
                                                      _ptr(workspace), workspace_bytes,
                                                      _ptr(stream))
+
+
+def specasr_accept_from_logits_static(ctx, tree, batch, logits_dev, argmax_dev, path_dev,
+                                      accept_len_dev, next_token_dev, stream=None):
+    return load_library().specasr_accept_from_logits_static(ctx, C.byref(tree), batch,
+                                                            _ptr(logits_dev), _ptr(argmax_dev),
+                                                            _ptr(path_dev), _ptr(accept_len_dev),
+                                                            _ptr(next_token_dev), _ptr(stream))
 
 
 def specasr_commit(ctx, kv, n_nodes, path, accept_len, workspace, workspace_bytes, stream=None):

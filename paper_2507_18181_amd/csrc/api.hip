@@ -9,6 +9,7 @@
 #include <new>
 #include <algorithm>
 #include <chrono>
+#include <mutex>
 #include <vector>
 
 #include "../../include/specasr.h"
@@ -94,7 +95,7 @@ namespace {
     }                                                       \
   } while (0)
 
-size_t meta_words(int rows_max, int batch) {
+constexpr size_t meta_words(int rows_max, int batch) {
   // token, seq, node, depth, pos, slot, parent, use_embed: 8 words per row; anc: 2 words per row;
   // kv_len, row_start, n_nodes: 3 words per sequence
   return (size_t)rows_max * 10 + (size_t)batch * 3;
@@ -1355,6 +1356,132 @@ specasr_status specasr_verify_tree(specasr_ctx *ctx, specasr_kv *kv, const speca
     out->next_token[b] = h[2 * BN + B + b];
     kv->kv_len[b] += out->accept_len[b];
   }
+  return SPECASR_OK;
+}
+
+// ---- an entry point that allocates nothing ------------------------------------------------------
+// specasr_accept_from_logits keeps the flattened tree metadata (per row: token, sequence, node,
+// depth, parent, ancestor mask; per sequence: first row, node count) in the caller's workspace and
+// fills it through pinned staging memory that the first call allocates.  The variant below keeps
+// that block in a device array of the library instead and fills it with a kernel that receives one
+// tree by value in its arguments, so nothing is allocated and nothing is copied.
+}  // extern "C"
+
+namespace {
+
+constexpr int kStaticMaxBatch = SPECASR_STATIC_MAX_BATCH;
+constexpr size_t kStaticScratchBytes =
+    (meta_words(kStaticMaxBatch * SPECASR_MAX_NODES, kStaticMaxBatch) * 4 + 255) / 256 * 256;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Address of `scratch` on each device (every GPU holds its own copy of the array); looked up once
+// per device, with that device current.
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mu;
+void *scratch_ptr[kMaxDevices] = {};
+
+specasr_status static_scratch(specasr_ctx *ctx, char **out) {
+  int dev = -1;
+  HIP_TRY(ctx, hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return SPECASR_E_UNSUPPORTED;
+  std::lock_guard<std::mutex> guard(scratch_mu);
+  if (!scratch_ptr[dev]) {
+    void *p = nullptr;
+    HIP_TRY(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return SPECASR_E_HIP;
+    scratch_ptr[dev] = p;
+  }
+  *out = static_cast<char *>(scratch_ptr[dev]);
+  return SPECASR_OK;
+}
+
+// One tree, passed by value in the kernel arguments.
+struct TreeByValue {
+  int32_t tokens[SPECASR_MAX_NODES];
+  int32_t parents[SPECASR_MAX_NODES];
+};
+
+// Step 0 of the path on the device: rows row_start .. row_start + n - 1 of the metadata block (the
+// layout build_step writes on the host, R = batch * max_nodes rows), lane = node.  The parent
+// array was validated on the host (parents[i] < i), so the walk to the root ends within n steps.
+__global__ __launch_bounds__(64) void tree_meta_kernel(TreeByValue t, int n, int seq, int row_start,
+                                                       int R, int batch, int32_t *w) {
+  const int i = threadIdx.x;
+  if (i == 0) {
+    w[10 * R + seq] = 0;                      // kv_len: acceptance has no cache position
+    w[10 * R + batch + seq] = row_start;
+    w[10 * R + 2 * batch + seq] = n;
+  }
+  if (i >= n) return;
+  int depth = 0;
+  uint64_t anc = 1ull << i;
+  for (int p = t.parents[i], hops = 0; p >= 0 && hops < SPECASR_MAX_NODES; p = t.parents[p], ++hops) {
+    anc |= 1ull << p;
+    ++depth;
+  }
+  const int r = row_start + i;
+  w[r] = t.tokens[i];
+  w[R + r] = seq;
+  w[2 * R + r] = i;
+  w[3 * R + r] = depth;
+  w[4 * R + r] = depth;                       // position and slot are zero-based here
+  w[5 * R + r] = i;
+  w[6 * R + r] = t.parents[i];
+  w[7 * R + r] = 0;
+  reinterpret_cast<uint64_t *>(w + 8 * R)[r] = anc;
+}
+
+}  // namespace
+
+extern "C" {
+
+specasr_status specasr_accept_from_logits_static(specasr_ctx *ctx, const specasr_tree *tree,
+                                                 int32_t batch, const float *logits_dev,
+                                                 int32_t *argmax_dev, int32_t *path_dev,
+                                                 int32_t *accept_len_dev, int32_t *next_token_dev,
+                                                 void *stream) {
+  if (!ctx || !logits_dev || !argmax_dev || !path_dev || !accept_len_dev || !next_token_dev)
+    return SPECASR_E_NULL;
+  specasr_status s = validate_tree(ctx, tree, batch, nullptr, 0, false);
+  if (s != SPECASR_OK) return s;
+  if (batch > kStaticMaxBatch) return SPECASR_E_UNSUPPORTED;  // beyond what the device array holds
+  char *sp = nullptr;
+  s = static_scratch(ctx, &sp);
+  if (s != SPECASR_OK) return s;
+  hipStream_t st = (hipStream_t)stream;
+  const specasr_config &c = ctx->cfg;
+  const int R = batch * c.max_nodes;
+  int32_t *w = reinterpret_cast<int32_t *>(sp);
+  int rows = 0;
+  for (int b = 0; b < batch; ++b) {
+    const int n = tree->n_nodes[b];
+    TreeByValue tv;
+    memset(&tv, 0, sizeof tv);
+    memcpy(tv.tokens, tree->tokens + (size_t)b * c.max_nodes, (size_t)n * 4);
+    memcpy(tv.parents, tree->parents + (size_t)b * c.max_nodes, (size_t)n * 4);
+    tree_meta_kernel<<<1, 64, 0, st>>>(tv, n, b, rows, R, batch, w);
+    rows += n;
+  }
+  StepMeta m;
+  m.token = w;
+  m.seq = w + R;
+  m.node = w + 2 * R;
+  m.depth = w + 3 * R;
+  m.pos = w + 4 * R;
+  m.slot = w + 5 * R;
+  m.parent = w + 6 * R;
+  m.use_embed = w + 7 * R;
+  m.anc = reinterpret_cast<const uint64_t *>(w + 8 * R);
+  m.kv_len = w + 10 * R;
+  m.row_start = m.kv_len + batch;
+  m.n_nodes = m.row_start + batch;
+  m.rows = rows;
+  m.batch = batch;
+  m.kv_len0 = 0;
+  m.n_nodes0 = tree->n_nodes[0];
+  launch_argmax(m, logits_dev, true, c.max_nodes, c.vocab, argmax_dev, st);
+  launch_accept(m, c.max_nodes, argmax_dev, path_dev, accept_len_dev, next_token_dev, st);
+  HIP_TRY(ctx, hipGetLastError());
   return SPECASR_OK;
 }
 

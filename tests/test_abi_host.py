@@ -202,3 +202,23 @@ def test_measurement_aids_need_the_mfma_path(ctx):
     assert B.specasr_stage_rows(ctx)[0] == B.SPECASR_E_UNSUPPORTED
     assert B.specasr_stage_rows(None)[0] == B.SPECASR_E_NULL
     assert B.specasr_uses_mfma(ctx, 200) == 0
+
+
+def test_static_entry_point_rejects_sizes_beyond_its_device_array(lib):
+    """specasr_accept_from_logits_static holds at most SPECASR_STATIC_MAX_BATCH trees: a larger
+    batch is refused on the host, before anything touches a GPU."""
+    cfg = wl.MODELS["tiny"]
+    sw, keep = _fake_weights(cfg)
+    nb = B.SPECASR_STATIC_MAX_BATCH + 1
+    rc, c = B.specasr_create(B.make_config(cfg, B.SPECASR_F32, 8, nb), sw)
+    assert rc == B.SPECASR_OK
+    tok = np.zeros((nb, 8), np.int32)
+    par = np.full((nb, 8), -1, np.int32)
+    nn = np.ones(nb, np.int32)
+    tree = B.make_tree(tok, par, nn)
+    fake = 0x1000
+    assert B.specasr_accept_from_logits_static(c, tree, nb, fake, fake, fake, fake, fake) == B.SPECASR_E_UNSUPPORTED
+    assert B.specasr_accept_from_logits_static(c, tree, nb, None, fake, fake, fake, fake) == B.SPECASR_E_NULL
+    par[0, 0] = 0                                   # invalid tree: reported as such, as by the workspace variant
+    assert B.specasr_accept_from_logits_static(c, tree, 2, fake, fake, fake, fake, fake) == B.SPECASR_E_TREE
+    B.specasr_destroy(c)
