@@ -17,8 +17,18 @@
  *    pointers are ordinary host memory.  The caller owns every buffer it passes
  *    (weights, KV cache, workspace, logits); they are borrowed for the call, the
  *    weights for the life of the context.  The library allocates device memory
- *    only inside specasr_create (the optional repacked weight copy) and a few KB
- *    of pinned host staging memory on the first call that needs it.
+ *    only inside specasr_create (the optional repacked weight copy).  Host-side
+ *    resources are created by the first call that needs them and released by
+ *    specasr_destroy: a few KB of pinned staging memory with one event per
+ *    staging slot (any call that uploads tree metadata), up to three internal
+ *    streams of default priority with fork/join events (calls that fall into
+ *    several sequence groups, chunked prefill) plus two events per layer
+ *    (chunked prefill), and event pairs for specasr_profile_stage.
+ *  - The library reads no environment variable after specasr_create.  That
+ *    call reads the development aids SPECASR_LANES, SPECASR_GEMM_SPLITS,
+ *    SPECASR_WIDE_SPLITS, SPECASR_ATTN_CHUNK and SPECASR_DEBUG once (forced kernel
+ *    plans for sweeps, diagnostics on stderr); results do not depend on them
+ *    beyond summation order, and a deployment sets none.
  *  - `stream` is a raw hipStream_t (NULL = the default stream).
  *  - A context is not thread-safe, and calls that use the same workspace must not overlap on
  *    the device: issue them on one stream, or order them with events.  Calls on different
@@ -65,6 +75,8 @@ typedef enum { SPECASR_F32 = 0, SPECASR_BF16 = 1 } specasr_dtype;
 /* flags for specasr_config.flags */
 #define SPECASR_FLAG_GENERIC_KERNELS 1u /* force the dtype-generic kernels (no MFMA path) */
 #define SPECASR_FLAG_NO_REPACK 2u       /* never make a repacked copy of the weights */
+#define SPECASR_FLAG_NO_WIDE 4u         /* no buffers for passes over more than 64 rows: such calls run as
+                                           groups of whole sequences, long prefills as chunks */
 
 #define SPECASR_MAX_NODES 64 /* one wavefront lane / one mask bit per tree node */
 
@@ -254,21 +266,6 @@ specasr_status specasr_commit(specasr_ctx *ctx, specasr_kv *kv, const int32_t *n
  * sequences with at most 64 rows each), 0 = the dtype-generic kernels (fp32 models, SPECASR_FLAG_GENERIC_KERNELS /
  * NO_REPACK, shapes the MFMA tiling does not cover). */
 int32_t specasr_uses_mfma(const specasr_ctx *ctx, int32_t rows);
-
-/* Measurement aid for benchmarks (no effect on results).  While enabled, every forward
- * launches ONE instance of the chosen projection GEMM (the layer rotates from call to call)
- * with a pair of HIP events that take the start and stop time of that dispatch on the caller's
- * stream (enable = 2: only the launches of the tiled kernel that prefill passes over more than 64
- * rows use).  specasr_stage_time waits for the recorded events and returns the accumulated
- * kernel milliseconds and the number of launches measured since profiling was enabled, plus the
- * weight bytes one such launch streams; specasr_stage_rows returns the activation rows summed
- * over the same launches (their algorithmic flops are 2 x rows x weight elements). */
-typedef enum { SPECASR_STAGE_QKV = 0, SPECASR_STAGE_O = 1, SPECASR_STAGE_GATE_UP = 2,
-               SPECASR_STAGE_DOWN = 3, SPECASR_STAGE_LM_HEAD = 4 } specasr_stage;
-specasr_status specasr_profile_stage(specasr_ctx *ctx, int32_t stage, int32_t enable);
-specasr_status specasr_stage_time(specasr_ctx *ctx, double *total_ms, int64_t *launches,
-                                  double *weight_bytes_per_launch);
-specasr_status specasr_stage_rows(specasr_ctx *ctx, int64_t *rows);
 
 const char *specasr_strerror(specasr_status s);
 /* hipError_t value of the last failing HIP call seen by this context (0 if none). */

@@ -1,0 +1,35 @@
+/*
+ * specasr_profile.h -- measurement aids of the tree-verification library.
+ *
+ * Not part of the verification path (include/specasr.h): these calls let a benchmark time one
+ * projection GEMM per forward with HIP events attached to that dispatch on the caller's stream.
+ * They have no effect on results.
+ */
+#ifndef SPECASR_PROFILE_H
+#define SPECASR_PROFILE_H
+
+#include "specasr.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* While enabled, every forward
+ * launches ONE instance of the chosen projection GEMM (the layer rotates from call to call)
+ * with a pair of HIP events that take the start and stop time of that dispatch on the caller's
+ * stream (enable = 2: only the launches of the tiled kernel that prefill passes over more than 64
+ * rows use).  specasr_stage_time waits for the recorded events and returns the accumulated
+ * kernel milliseconds and the number of launches measured since profiling was enabled, plus the
+ * weight bytes one such launch streams; specasr_stage_rows returns the activation rows summed
+ * over the same launches (their algorithmic flops are 2 x rows x weight elements). */
+typedef enum { SPECASR_STAGE_QKV = 0, SPECASR_STAGE_O = 1, SPECASR_STAGE_GATE_UP = 2,
+               SPECASR_STAGE_DOWN = 3, SPECASR_STAGE_LM_HEAD = 4 } specasr_stage;
+specasr_status specasr_profile_stage(specasr_ctx *ctx, int32_t stage, int32_t enable);
+specasr_status specasr_stage_time(specasr_ctx *ctx, double *total_ms, int64_t *launches,
+                                  double *weight_bytes_per_launch);
+specasr_status specasr_stage_rows(specasr_ctx *ctx, int64_t *rows);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECASR_PROFILE_H */

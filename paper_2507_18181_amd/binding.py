@@ -26,6 +26,7 @@ SPECASR_E_PATH = -8
 SPECASR_F32, SPECASR_BF16 = 0, 1
 SPECASR_FLAG_GENERIC_KERNELS = 1
 SPECASR_FLAG_NO_REPACK = 2
+SPECASR_FLAG_NO_WIDE = 4
 SPECASR_MAX_NODES = 64
 SPECASR_STATIC_MAX_BATCH = 16
 

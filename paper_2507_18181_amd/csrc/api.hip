@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "../../include/specasr.h"
+#include "../../include/specasr_profile.h"
 #include "kernels.h"
 #include "kernels_mfma.h"
 
@@ -48,6 +49,23 @@ struct PackedLayer {
 
 constexpr int kMaxLanes = 4;  // streams a multi-group call is spread over (lane 0 = the caller's)
 
+// Development aids: environment variables that specasr_create reads ONCE into the context (no
+// call reads the environment afterwards).  A deployment sets none of them.
+struct Tuning {
+  int lanes = kMaxLanes;                     // SPECASR_LANES: streams for multi-group calls, 1..4
+  int gemm_splits[5] = {0, 0, 0, 0, 0};      // SPECASR_GEMM_SPLITS "qkv,o,gate_up,down,lm_head": k-splits of the skinny GEMMs (0: planner)
+  int wide_splits[5] = {0, 0, 0, 0, 0};      // SPECASR_WIDE_SPLITS: the same for the tiled GEMM of wide passes
+  int attn_chunk = 0;                        // SPECASR_ATTN_CHUNK: lower bound of the attention key chunk
+  bool debug = false;                        // SPECASR_DEBUG: print kernel plans and host timings to stderr
+  void read_env() {
+    if (const char *e = getenv("SPECASR_LANES")) { const int v = atoi(e); lanes = v < 1 ? 1 : v > kMaxLanes ? kMaxLanes : v; }
+    if (const char *e = getenv("SPECASR_GEMM_SPLITS")) sscanf(e, "%d,%d,%d,%d,%d", &gemm_splits[0], &gemm_splits[1], &gemm_splits[2], &gemm_splits[3], &gemm_splits[4]);
+    if (const char *e = getenv("SPECASR_WIDE_SPLITS")) sscanf(e, "%d,%d,%d,%d,%d", &wide_splits[0], &wide_splits[1], &wide_splits[2], &wide_splits[3], &wide_splits[4]);
+    if (const char *e = getenv("SPECASR_ATTN_CHUNK")) attn_chunk = atoi(e);
+    debug = getenv("SPECASR_DEBUG") != nullptr;
+  }
+};
+
 struct specasr_ctx {
   bool fast = false;  // bf16 MFMA path available (weights repacked)
   std::vector<PackedLayer> packed;
@@ -64,6 +82,7 @@ struct specasr_ctx {
   size_t prof_used = 0;             // events recorded and not yet accumulated
   double prof_ms = 0.0;
   int64_t prof_launches = 0, prof_calls = 0;  // per-row-count-independent bound of the partial-sum buffer, in floats per row
+  Tuning tune;
   specasr_config cfg;
   ModelDims md;
   specasr_weights w;
@@ -372,10 +391,10 @@ specasr_status upload_meta(specasr_ctx *ctx, const HostStep &hs, char *ws, const
 
 // A call that can fall into several sequence groups gets one workspace per lane (everything but the
 // result block, which the lanes share).  Measured on config 4 (16 utterances, 8 groups): 13.8 ms
-// with one lane, 10.6 with two, 9.0 with three or four (tuning aid: SPECASR_LANES).
+// with one lane, 10.6 with two, 9.0 with three or four (development aid: Tuning::lanes).
 int ws_lanes(const specasr_ctx *ctx, int batch) {
   if (!ctx->fast) return 1;
-  static const int want = [] { const char *e = getenv("SPECASR_LANES"); int v = e ? atoi(e) : kMaxLanes; return v < 1 ? 1 : v > kMaxLanes ? kMaxLanes : v; }();
+  const int want = ctx->tune.lanes;
   if (want == 1) return 1;
   const int groups_max = (int)(((size_t)batch * ctx->cfg.max_nodes + 63) / 64);  // groups at full trees
   const int n = groups_max < want ? groups_max : want;
@@ -528,9 +547,9 @@ struct LayerSync {
 // rows, a wide prefill pass: tiled GEMMs bound by the matrix cores).  Residual stream, norms, softmax and all
 // accumulators stay fp32; only the MFMA operands (normalised activations, attention output,
 // SwiGLU output) are rounded to bf16.
-void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_kv *kv,
-                  const specasr_tree *tree, char *ws, const WsLayout &L, const HostStep &hs,
-                  const ReadOut &ro, const LayerSync &sync, hipStream_t st) {
+specasr_status forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_kv *kv,
+                            const specasr_tree *tree, char *ws, const WsLayout &L, const HostStep &hs,
+                            const ReadOut &ro, const LayerSync &sync, hipStream_t st) {
   int32_t *argmax_dev = ro.argmax;
   float *logits_dev = ro.logits;
   const ModelDims &md = ctx->md;
@@ -562,29 +581,24 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
       while (S > 1 && (size_t)S * pm[i]->ldo * part_rows_pad(R) > ctx->wide_part_floats) S /= 2;
       pls[i]->n_splits = S;
     }
-    if (const char *e = getenv("SPECASR_WIDE_SPLITS")) {  // tuning aid: "qkv,o,gate_up,down,lm_head" split counts
-      int v[5] = {0, 0, 0, 0, 0};
-      sscanf(e, "%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4]);
-      for (int i = 0; i < 5; ++i)
-        if (v[i] >= 1 && v[i] <= pm[i]->ksteps && (size_t)v[i] * pm[i]->ldo * part_rows_pad(R) <= ctx->wide_part_floats)
-          pls[i]->n_splits = v[i];
+    for (int i = 0; i < 5; ++i) {  // development aid: forced split counts
+      const int v = ctx->tune.wide_splits[i];
+      if (v >= 1 && v <= pm[i]->ksteps && (size_t)v * pm[i]->ldo * part_rows_pad(R) <= ctx->wide_part_floats)
+        pls[i]->n_splits = v;
     }
-  }
-
-  if (const char *e = wide ? nullptr : getenv("SPECASR_GEMM_SPLITS")) {  // tuning aid: "qkv,o,gate_up,down,lm_head" split counts
-    int v[5] = {0, 0, 0, 0, 0};
-    sscanf(e, "%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4]);
+  } else {
     GemmPlan *pls[5] = {&pl_qkv, &pl_o, &pl_gu, &pl_dn, &pl_lm};
     const PackedMatrix *pm[5] = {&p0.qkv, &p0.o, &p0.gu, &p0.down, &ctx->lm_head};
-    for (int i = 0; i < 5; ++i) {
-      if (v[i] < 1 || ctx->n_cu % v[i]) continue;
-      const int len = ((pm[i]->ksteps + v[i] - 1) / v[i] + 7) / 8;
-      if (len > (nb == 1 ? 16 : 8) || (size_t)v[i] * pm[i]->ldo > ctx->part_floats) continue;
-      pls[i]->n_splits = v[i];
+    for (int i = 0; i < 5; ++i) {  // development aid: forced split counts
+      const int v = ctx->tune.gemm_splits[i];
+      if (v < 1 || ctx->n_cu % v) continue;
+      const int len = ((pm[i]->ksteps + v - 1) / v + 7) / 8;
+      if (len > (nb == 1 ? 16 : 8) || (size_t)v * pm[i]->ldo > ctx->part_floats) continue;
+      pls[i]->n_splits = v;
       pls[i]->lw = nb == 1 ? (len <= 4 ? 4 : len <= 8 ? 8 : len <= 12 ? 12 : 16) : (len <= 4 ? 4 : 8);
     }
   }
-  if (getenv("SPECASR_DEBUG")) {
+  if (ctx->tune.debug) {
     const GemmPlan *pls[5] = {&pl_qkv, &pl_o, &pl_gu, &pl_dn, &pl_lm};
     const char *nm[5] = {"qkv", "o", "gate_up", "down", "lm_head"};
     const PackedMatrix *pm[5] = {&p0.qkv, &p0.o, &p0.gu, &p0.down, &ctx->lm_head};
@@ -604,14 +618,14 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
     gemm_stage(ctx, SPECASR_STAGE_QKV, pl, pk.qkv, hb, R, part, pl_qkv, st);
     if (mfma_attn) {
       launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, nrm, ctx->col_k, ctx->col_v, cs, nullptr, qb, qb_lo, kv->k, kv->v, st);
-      if (sync.record) (void)hipEventRecord(sync.record[l], st);
-      if (sync.wait) (void)hipStreamWaitEvent(st, sync.wait[l], 0);
+      if (sync.record) HIP_TRY(ctx, hipEventRecord(sync.record[l], st));
+      if (sync.wait) HIP_TRY(ctx, hipStreamWaitEvent(st, sync.wait[l], 0));
       launch_tree_attention(m, md, g, l, hs.max_total_keys, hs.max_seq_nodes, qb, qb_lo, kv->k, kv->v,
-                            (float *)(ws + L.attn_o), (float *)(ws + L.attn_ml), attb, attb_lo, nb, st);
+                            (float *)(ws + L.attn_o), (float *)(ws + L.attn_ml), attb, attb_lo, nb, ctx->tune.attn_chunk, st);
     } else {
       launch_qkv_finish(m, md, g, l, part, pl_qkv.n_splits, pk.qkv.ldo, nrm, ctx->col_k, ctx->col_v, cs, q, nullptr, nullptr, kv->k, kv->v, st);
-      if (sync.record) (void)hipEventRecord(sync.record[l], st);
-      if (sync.wait) (void)hipStreamWaitEvent(st, sync.wait[l], 0);
+      if (sync.record) HIP_TRY(ctx, hipEventRecord(sync.record[l], st));
+      if (sync.wait) HIP_TRY(ctx, hipStreamWaitEvent(st, sync.wait[l], 0));
       launch_attention_generic(m, md, g, l, q, kv->k, kv->v, att, st);
       launch_to_bf16(att, R, dq, attb, attb_lo, st);
     }
@@ -623,7 +637,7 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
     pending = pl_dn.n_splits;
     pending_ld = pk.down.ldo;
   }
-  if (ro.none()) return;
+  if (ro.none()) return SPECASR_OK;
   if (ro.first_row > 0) {
     // views of the last rows: residual, pending partial sums and row statistics start R0 rows in;
     // their planes are packed from row 0 again and go through the skinny LM head
@@ -643,7 +657,7 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
     else
       launch_logits_argmax(ms, part, pls.n_splits, ctx->lm_head.ldo, nrs, V, ctx->cfg.max_nodes, logits_dev,
                            (float *)(ws + L.blk_val), (int *)(ws + L.blk_idx), argmax_dev, st);
-    return;
+    return SPECASR_OK;
   }
   launch_residual_gain(x, part, pending, R, pending_ld, ctx->w.final_norm, d, hb, hb_lo, nb, ssq, st);
   gemm_stage(ctx, SPECASR_STAGE_LM_HEAD, true, ctx->lm_head, hb, R, part, pl_lm, st);
@@ -653,6 +667,7 @@ void forward_fast(specasr_ctx *ctx, const StepMeta &m, const KvGeom &g, specasr_
   else
     launch_logits_argmax(m, part, pl_lm.n_splits, ctx->lm_head.ldo, nrm, V, ctx->cfg.max_nodes, logits_dev,
                          (float *)(ws + L.blk_val), (int *)(ws + L.blk_idx), argmax_dev, st);
+  return SPECASR_OK;
 }
 
 specasr_status forward_common(specasr_ctx *ctx, specasr_kv *kv, const specasr_tree *tree,
@@ -662,9 +677,10 @@ specasr_status forward_common(specasr_ctx *ctx, specasr_kv *kv, const specasr_tr
   KvGeom g{kv->capacity, ctx->md.n_layers, ctx->md.n_kv_heads, ctx->md.head_dim};
   g.shared_cache = shared_cache ? 1 : 0;
   StepMeta m = device_meta(ctx, ws, L, hs.batch, hs);
-  if (ctx->fast && (m.rows <= 64 || wide_ws))
-    forward_fast(ctx, m, g, kv, tree, ws, L, hs, ro, sync, st);
-  else
+  if (ctx->fast && (m.rows <= 64 || wide_ws)) {
+    const specasr_status s = forward_fast(ctx, m, g, kv, tree, ws, L, hs, ro, sync, st);
+    if (s != SPECASR_OK) return s;
+  } else
     forward_generic(ctx, m, g, kv, tree, ws, L, ro, st);
   HIP_TRY(ctx, hipGetLastError());
   return SPECASR_OK;
@@ -683,19 +699,13 @@ struct SeqGroup {
 // the dtype-generic kernels take the whole call at once.
 // Where the context has the wide buffers, a call with more than 64 rows is ONE group on the wide
 // kernels instead: the weights are streamed once, not once per group (7B, 2 x 64 nodes: 6.8 ms
-// against 8.5 in two groups; tuning aid: SPECASR_WIDE_MIN_ROWS raises the threshold).
-int wide_min_rows() {
-  const char *e = getenv("SPECASR_WIDE_MIN_ROWS");
-  const int x = e ? atoi(e) : 65;
-  return x < 65 ? 65 : x;
-}
-
+// against 8.5 in two groups).  SPECASR_FLAG_NO_WIDE creates a context without them.
 std::vector<SeqGroup> split_call(const specasr_ctx *ctx, const specasr_kv *kv, const specasr_tree *tree,
                                  bool *wide) {
   const specasr_config &c = ctx->cfg;
   int total = 0;
   for (int b = 0; b < kv->batch; ++b) total += tree->n_nodes[b];
-  *wide = ctx->fast && ctx->wide_part_floats > 0 && total >= wide_min_rows();
+  *wide = ctx->fast && ctx->wide_part_floats > 0 && total > 64;
   const size_t esz = c.dtype == SPECASR_BF16 ? 2 : 4;
   const size_t seq_kv_bytes = (size_t)c.n_layers * c.n_kv_heads * (size_t)kv->capacity * c.head_dim * esz;
   std::vector<SeqGroup> out;
@@ -781,8 +791,7 @@ specasr_status build_packed(specasr_ctx *ctx) {
     }
   ctx->part_floats = bound;
   // wide passes: more than 64 rows at once -- prefill pieces or the trees of a batch (MFMA attention only)
-  const char *wide_env = getenv("SPECASR_WIDE");  // read at context creation: "0" keeps this context off the wide kernels
-  const bool wide_off = wide_env && atoi(wide_env) == 0;
+  const bool wide_off = (c.flags & SPECASR_FLAG_NO_WIDE) != 0;
   if (tree_attention_supported(c.head_dim) && !wide_off) {
     size_t wb = 0;
     const int rows_max = wide_seqs(c.max_batch) * c.max_nodes;
@@ -906,6 +915,7 @@ specasr_status specasr_create(const specasr_config *cfg, const specasr_weights *
   ctx->cfg = c;
   ctx->md = ModelDims{c.n_layers, c.d_model, c.n_heads, c.n_kv_heads, c.head_dim, c.d_ffn,
                       c.vocab, c.rms_eps, c.rope_theta, c.dtype};
+  ctx->tune.read_env();
   ctx->layers.assign(weights->layers, weights->layers + c.n_layers);
   ctx->w = *weights;
   ctx->w.layers = ctx->layers.data();
@@ -1303,7 +1313,7 @@ specasr_status specasr_verify_tree(specasr_ctx *ctx, specasr_kv *kv, const speca
   hipStream_t st = (hipStream_t)stream;
   char *ws = (char *)workspace;
   const WsLayout L = ws_layout(ctx, B);
-  static const bool debug_timing = getenv("SPECASR_DEBUG") != nullptr;
+  const bool debug_timing = ctx->tune.debug;
   const auto t_begin = std::chrono::steady_clock::now();
   int32_t *o = reinterpret_cast<int32_t *>(ws + L.outs);
   const size_t BN = (size_t)B * c.max_nodes, MN = (size_t)c.max_nodes;

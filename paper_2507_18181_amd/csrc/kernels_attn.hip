@@ -16,8 +16,6 @@
 //                                                   which is exactly how the lanes already hold P
 //
 // Partial (unnormalised) outputs per key chunk are merged by a second small kernel.
-#include <cstdlib>
-
 #include "kernels.h"
 #include "kernels_mfma.h"
 
@@ -368,7 +366,7 @@ __global__ void tree_attention_merge_kernel(StepMeta m, int H, int HD, int chunk
 
 template <int HD>
 static void launch_attn_hd(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
-                           int max_seq_nodes, int chunk_keys, int n_chunks, bool pair,
+                           int max_seq_nodes, int chunk_keys, int n_chunks,
                            const uint16_t *qb, const uint16_t *qb_lo, const void *kc, const void *vc,
                            float *o_part, float *ml_part, uint16_t *out, uint16_t *out_lo, int nb,
                            hipStream_t st) {
@@ -381,17 +379,8 @@ static void launch_attn_hd(const StepMeta &m, const ModelDims &md, const KvGeom 
     const size_t mg = (size_t)4 * rgw * (HD / 32) * 4096 + (size_t)4 * rgw * 32 * 2 * 4;
     return vt > mg ? vt : mg;
   };
-  if constexpr (HD > 64) {
-    dim3 grid((n_chunks * md.n_kv_heads + 7) / 8 * 8 * row_groups, 1, m.batch);
-    tree_attention_kernel<HD, 1><<<grid, 256, lds_bytes(1), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, row_groups, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, n_chunks, o_part, ml_part, direct ? out : nullptr, direct ? out_lo : nullptr, nb);
-  } else if (!pair) {
-    dim3 grid((n_chunks * md.n_kv_heads + 7) / 8 * 8 * row_groups, 1, m.batch);
-    tree_attention_kernel<HD, 1><<<grid, 256, lds_bytes(1), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, row_groups, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, n_chunks, o_part, ml_part, direct ? out : nullptr, direct ? out_lo : nullptr, nb);
-  } else {
-    const int n_rgb = (row_groups + 1) / 2;
-    dim3 grid((n_chunks * md.n_kv_heads + 7) / 8 * 8 * n_rgb, 1, m.batch);
-    tree_attention_kernel<HD, 2><<<grid, 256, lds_bytes(2), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, n_rgb, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, n_chunks, o_part, ml_part, direct ? out : nullptr, direct ? out_lo : nullptr, nb);
-  }
+  dim3 grid((n_chunks * md.n_kv_heads + 7) / 8 * 8 * row_groups, 1, m.batch);
+  tree_attention_kernel<HD, 1><<<grid, 256, lds_bytes(1), st>>>(m, g, layer, md.n_heads, md.n_kv_heads, row_groups, qb, qb_lo, (const uint16_t *)kc, (const uint16_t *)vc, chunk_keys, n_chunks, o_part, ml_part, direct ? out : nullptr, direct ? out_lo : nullptr, nb);
   if (direct) return;
   dim3 mgrid(md.n_heads, m.rows);
   tree_attention_merge_kernel<<<mgrid, HD, 0, st>>>(m, md.n_heads, HD, chunk_keys, o_part, ml_part, out, out_lo, nb);
@@ -402,12 +391,10 @@ bool tree_attention_supported(int head_dim) { return head_dim == 64 || head_dim 
 int tree_attention_max_chunks(int n_kv_heads) { return 256 / n_kv_heads + 2; }
 
 hipError_t tree_attention_set_lds_limit() {
-  const int big = 4 * 2 * 4 * 4096 + 4 * 2 * 32 * 2 * 4;  // RGW = 2, head_dim 128
+  const int big = 4 * 4 * 4096 + 4 * 32 * 2 * 4;  // merge area at head_dim 128: the larger of the two uses
   hipError_t e = hipFuncSetAttribute((const void *)tree_attention_kernel<128, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute((const void *)tree_attention_kernel<64, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute((const void *)tree_attention_kernel<64, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
+  return hipFuncSetAttribute((const void *)tree_attention_kernel<64, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, big);
 }
 
 // Key-chunk size (a multiple of 32).  One sequence: ~256 workgroups (one per compute unit) over
@@ -418,7 +405,7 @@ hipError_t tree_attention_set_lds_limit() {
 // workgroups if all were as long as the longest, at least 128 keys (one tile per wavefront) -- and
 // the short ones simply need fewer of them (1.1B, 16 utterances: 67 us against 80); the number of
 // chunks stays within what the wide workspace holds (128 / n_kv_heads + 1).
-int tree_attention_chunk_keys(int max_total_keys, int n_kv_heads, int batch, int row_group_blocks) {
+int tree_attention_chunk_keys(int max_total_keys, int n_kv_heads, int batch, int row_group_blocks, int min_chunk_keys) {
   const long target = batch > 1 ? 1024 : 256;
   long want = ((long)max_total_keys * n_kv_heads * batch * row_group_blocks + target - 1) / target;
   long ck = (want + 31) / 32 * 32;
@@ -433,33 +420,27 @@ int tree_attention_chunk_keys(int max_total_keys, int n_kv_heads, int batch, int
     const long ck_min = ((max_total_keys + max_chunks - 1) / max_chunks + 31) / 32 * 32;
     if (ck < ck_min) ck = ck_min;
   }
-  if (const char *e = getenv("SPECASR_ATTN_CHUNK")) {  // tuning aid: never below the automatic size
-    const long v = atol(e) / 32 * 32;
-    if (v > ck) ck = v;
-  }
+  if (min_chunk_keys / 32 * 32 > ck) ck = min_chunk_keys / 32 * 32;  // development aid: never below the automatic size
   return (int)ck;
 }
 
 void launch_tree_attention(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
                            int max_total_keys, int max_seq_nodes, const uint16_t *qb,
                            const uint16_t *qb_lo, const void *kc, const void *vc, float *o_part,
-                           float *ml_part, uint16_t *out, uint16_t *out_lo, int nb, hipStream_t st) {
+                           float *ml_part, uint16_t *out, uint16_t *out_lo, int nb, int min_chunk_keys,
+                           hipStream_t st) {
   const int G = md.n_heads / md.n_kv_heads;
+  // One query row group (32 rows) per workgroup.  Two per workgroup would halve the key traffic
+  // (head_dim 64: the accumulators would fit), but the keys of a head are L2 hits after their
+  // first use and the kernel is bound by its softmax arithmetic: measured slower wherever it was
+  // tried (16 utterances on the 1.1B model: 43 against 38 us).
   const int row_groups = (G * max_seq_nodes + 31) / 32;
-  // Two query row groups per workgroup halve the key traffic (head_dim 64 only: their accumulators
-  // fit the register file) -- but the keys of a head are L2 hits after their first use and the
-  // kernel is bound by its softmax arithmetic, so one row group per workgroup, twice the
-  // workgroups and half the registers measured faster wherever it was tried (16 utterances on the
-  // 1.1B model: 38 against 43 us).  Kept as a tuning aid: SPECASR_ATTN_PAIR=1.
-  bool pair = false;
-  if (const char *e = getenv("SPECASR_ATTN_PAIR")) pair = atoi(e) != 0 && row_groups > 1 && md.head_dim <= 64;
-  const int n_rgb = pair ? (row_groups + 1) / 2 : row_groups;
-  const int ck = tree_attention_chunk_keys(max_total_keys, md.n_kv_heads, m.batch, n_rgb);
+  const int ck = tree_attention_chunk_keys(max_total_keys, md.n_kv_heads, m.batch, row_groups, min_chunk_keys);
   const int n_chunks = (max_total_keys + ck - 1) / ck;
   if (md.head_dim == 64)
-    launch_attn_hd<64>(m, md, g, layer, max_seq_nodes, ck, n_chunks, pair, qb, qb_lo, kc, vc, o_part, ml_part, out, out_lo, nb, st);
+    launch_attn_hd<64>(m, md, g, layer, max_seq_nodes, ck, n_chunks, qb, qb_lo, kc, vc, o_part, ml_part, out, out_lo, nb, st);
   else
-    launch_attn_hd<128>(m, md, g, layer, max_seq_nodes, ck, n_chunks, pair, qb, qb_lo, kc, vc, o_part, ml_part, out, out_lo, nb, st);
+    launch_attn_hd<128>(m, md, g, layer, max_seq_nodes, ck, n_chunks, qb, qb_lo, kc, vc, o_part, ml_part, out, out_lo, nb, st);
 }
 
 }  // namespace specasr

@@ -53,6 +53,7 @@ hipError_t tree_attention_set_lds_limit();
 void launch_tree_attention(const StepMeta &m, const ModelDims &md, const KvGeom &g, int layer,
                            int max_total_keys, int max_seq_nodes, const uint16_t *qb,
                            const uint16_t *qb_lo, const void *kc, const void *vc, float *o_part,
-                           float *ml_part, uint16_t *out, uint16_t *out_lo, int nb, hipStream_t st);
+                           float *ml_part, uint16_t *out, uint16_t *out_lo, int nb, int min_chunk_keys,
+                           hipStream_t st);
 
 }  // namespace specasr

@@ -59,6 +59,11 @@ class SpecDecoder:
         self.max_nodes = min(target.max_nodes, draft.max_nodes)
         self.kept = {}            # absolute position -> token of the previous round's rejected suffix
         self.stats = RoundStats()
+        # Optional recording for tests: set to a list and every round appends a dict with its
+        # inputs (root, pos0, kept), its tree and the draft read-out of every node it consulted,
+        # keyed by the node's root path (a causal model's read-out depends on nothing else).
+        self.trace = None
+        self._read = {}
 
     # -- draft side ---------------------------------------------------------------------------
     def _draft_forward(self, tokens, parents):
@@ -67,7 +72,15 @@ class SpecDecoder:
             raise RuntimeError("draft forward failed: status %d" % out["status"])
         self.stats.draft_forwards += 1
         self._stale = False                           # every node now has its draft-side K/V row
-        return out["top2"][0].cpu().numpy(), out["prob"][0].cpu().numpy()
+        top2, prob = out["top2"][0].cpu().numpy(), out["prob"][0].cpu().numpy()
+        if self.trace is not None:
+            for i in range(len(tokens)):
+                path, j = [], i
+                while j >= 0:
+                    path.append(int(tokens[j]))
+                    j = parents[j]
+                self._read[tuple(reversed(path))] = (int(top2[i, 0]), int(top2[i, 1]), float(prob[i]))
+        return top2, prob
 
     def _build_tree(self):
         """Returns (tokens, parents, trunk node ids)."""
@@ -153,6 +166,8 @@ class SpecDecoder:
         """Drafts a tree, verifies it, commits the accepted path on both sides.  Returns the tokens
         this round adds to the output: the accepted draft tokens, then the target's own token."""
         pos0 = int(self.t.kv_len[0])
+        kept_in, self._read = dict(self.kept), {}
+        recycled_before = self.stats.recycled
         tokens, parents, trunk = self._build_tree()
         n = len(tokens)
         out = self.t.verify_tree([np.asarray(tokens, np.int32)], [np.asarray(parents, np.int32)])
@@ -173,6 +188,11 @@ class SpecDecoder:
         # path covers positions pos0 .. pos0+alen-1, the target's token takes pos0+alen
         if self.recycle:
             self.kept = {pos0 + i: tokens[trunk[i]] for i in range(alen + 1, len(trunk))}
+        if self.trace is not None:
+            self.trace.append(dict(root=tokens[0], pos0=pos0, kept=kept_in, tokens=list(tokens),
+                                   parents=list(parents), trunk=list(trunk), read=self._read,
+                                   accept_len=alen, path=path, kept_out=dict(self.kept),
+                                   recycled=self.stats.recycled - recycled_before))
         self.root = nxt
         return [tokens[v] for v in path[1:]] + [nxt]
 

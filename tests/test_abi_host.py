@@ -39,7 +39,7 @@ def ctx(lib):
 
 
 def test_exports_match_header(lib):
-    hdr = open(os.path.join(ROOT, "include", "specasr.h")).read()
+    hdr = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("specasr.h", "specasr_profile.h"))
     declared = set(re.findall(r"\b(specasr_[a-z0-9_]+)\s*\(", hdr))
     assert declared == set(B.EXPORTS)
     for name in declared:

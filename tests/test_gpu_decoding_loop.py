@@ -9,6 +9,10 @@ import oracle
 import workload as wl
 from parity_util import TOL_F32
 
+# bf16 runs: largest logit error measured between the MFMA path and the oracle reading the same
+# bf16 weights and cache is 2.3e-4 of the row maximum (1.1B .. 13B models; 1e-5 on the tiny one)
+TOL_LOOP_BF16 = 2.5e-4
+
 pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
@@ -23,31 +27,44 @@ def _peaky(w, k):
     return w
 
 
-def _oracle_greedy(cfg, w, audio, text, n_new):
-    """(tokens, decisive flags): the target's greedy continuation after the prompt."""
+def _store(w, dtype):
+    """fp32 weight dict -> storage form of the run (bf16: rounded once, as bit patterns)."""
+    if dtype == "f32":
+        return w
+    out = {k: wl.bf16_bits(v) for k, v in w.items() if k != "layers"}
+    out["layers"] = [{k: wl.bf16_bits(v) for k, v in lw.items()} for lw in w["layers"]]
+    return out
+
+
+def _oracle_greedy(cfg, w, audio, text, n_new, dtype="f32"):
+    """(tokens, decisive flags): the target's greedy continuation after the prompt.  For a bf16 run
+    the oracle reads the same rounded weights and keeps its cache in bf16 storage as well."""
     om = oracle.OracleModel(cfg, w)
-    kc, vc = om.empty_cache(CAP)
+    kc, vc = om.empty_cache(CAP, np.float64 if dtype == "f32" else np.uint16)
+    tol = TOL_F32 if dtype == "f32" else TOL_LOOP_BF16
     L, _ = om.prefill(kc, vc, 0, audio.astype(np.float64), text[:-1])
     t, toks, dec = int(text[-1]), [], []
     for _ in range(n_new):
         r = om.tree_forward(kc, vc, L, np.array([t], np.int32), np.array([-1], np.int32))
         L = om.commit(kc, vc, L, r["ktree"], r["vtree"], [0])
-        # fp32 model: the GPU's logits are within TOL_F32 * max|logit| of these, so a gap of ten
-        # times that cannot flip
+        # the GPU's logits are within tol * max|logit| of these (asserted by the parity tests: 1e-4
+        # for fp32 models; bf16 ones: see TOL_LOOP_BF16), so a gap of ten times that cannot flip
         srt = np.sort(r["logits"][0])
-        dec.append(srt[-1] - srt[-2] > 10 * TOL_F32 * np.abs(srt).max())
+        dec.append(srt[-1] - srt[-2] > 10 * tol * np.abs(srt).max())
         t = int(r["amax"][0])
         toks.append(t)
     return toks, dec
 
 
-def _pair(cfg, w_target, w_draft, audio, text):
+def _pair(cfg, w_target, w_draft, audio, text, dtype="f32"):
+    from paper_2507_18181_amd import binding as B
     from paper_2507_18181_amd.runtime import Verifier
     vers = []
     for w in (w_target, w_draft):
-        v = Verifier(cfg, w, "f32", max_nodes=64, capacity=CAP)
-        emb = torch.zeros((1, len(audio) + len(text) - 1, cfg["d_model"]), dtype=torch.float32, device=v.device)
-        emb[0, :len(audio)] = torch.from_numpy(audio).to(v.device)
+        v = Verifier(cfg, w, dtype, max_nodes=64, capacity=CAP)
+        assert B.specasr_uses_mfma(v.ctx, 64) == (1 if dtype == "bf16" else 0)
+        emb = torch.zeros((1, len(audio) + len(text) - 1, cfg["d_model"]), dtype=v.tdtype, device=v.device)
+        emb[0, :len(audio)] = torch.from_numpy(audio).to(v.device).to(v.tdtype)
         tok = np.concatenate([np.zeros(len(audio), np.int32), text[:-1]])
         out = v.prefill([tok], embeds=emb, use_embed=[[1] * len(audio) + [0] * (len(text) - 1)], want_next=False)
         assert out["status"] == 0
@@ -63,12 +80,34 @@ def _check_lossless(got, want, dec):
     return stop
 
 
+def _check_rounds_against_the_oracle_constructor(sd, mode, threshold):
+    """Every round's tree must be the one the oracle's plain constructor (oracle/sparse_tree.py:
+    Sec. IV-A truncation, IV-B merging, IV-C second pass) builds from the SAME draft read-outs,
+    the same root and the same kept suffix -- node for node -- and the suffix kept for the next
+    round must be the oracle's."""
+    from oracle import sparse_tree as ost
+    prm = ost.Params(max_draft=sd.max_draft, threshold=threshold, mode=mode, max_branches=sd.max_branches,
+                     branch_depth=sd.branch_depth, max_nodes=sd.max_nodes, recycle=sd.recycle)
+    assert len(sd.trace) == sd.stats.rounds
+    for i, t in enumerate(sd.trace):
+        r = ost.build_round(lambda path: t["read"][path], t["root"], t["pos0"], t["kept"], prm)
+        assert r.tokens == t["tokens"] and r.parents == t["parents"] and r.trunk == t["trunk"], "round %d" % i
+        assert r.recycled == t["recycled"]
+        want_kept = ost.kept_after([t["tokens"][v] for v in t["trunk"]], t["pos0"], t["accept_len"])
+        assert want_kept == t["kept_out"], "round %d" % i
+        # acceptance as the oracle defines it on the target's own argmax is covered by the verify
+        # tests; here: the accepted path is a root path of this tree
+        assert t["path"][0] == 0 and all(t["parents"][b] == a for a, b in zip(t["path"][:-1], t["path"][1:]))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("mode", ["asp", "tsp"])
 @pytest.mark.parametrize("kind", ["self", "foreign", "noisy"])
-def test_loop_reproduces_the_targets_greedy_decoding(mode, kind):
+def test_loop_reproduces_the_targets_greedy_decoding(mode, kind, dtype):
     """Three draft models for one target: the target itself (every draft accepted), an unrelated
     model (nothing but the root accepted), the target with 3 % weight noise (partial acceptance,
-    branches and recycling in play).  In every case the output is the oracle's greedy decoding."""
+    branches and recycling in play).  In every case the output is the oracle's greedy decoding,
+    on the dtype-generic kernels (fp32 model) and on the bf16 MFMA kernels the benchmark runs."""
     from paper_2507_18181_amd.decoding import SpecDecoder
     cfg = wl.MODELS["tiny"]
     w_t = _peaky(wl.make_weights(cfg, 321, "f32"), 6.0)   # a seed whose 90 greedy steps are all decisive
@@ -83,17 +122,24 @@ def test_loop_reproduces_the_targets_greedy_decoding(mode, kind):
         w_d["layers"] = [{k: (v * (1 + 0.03 * rng.standard_normal(v.shape))).astype(np.float32)
                           for k, v in lw.items()} for lw in w_t["layers"]]
     audio, text = wl.make_prefix_inputs(cfg, 313, 20, 6)
+    if dtype == "bf16":
+        audio = wl.bf16_to_f32(wl.bf16_bits(audio.astype(np.float32)))      # the embedding rows both sides read
+    w_t, w_d = _store(w_t, dtype), _store(w_d, dtype)
     n_new = 90
-    want, dec = _oracle_greedy(cfg, w_t, audio, text, n_new)
-    target, draft = _pair(cfg, w_t, w_d, audio, text)
+    want, dec = _oracle_greedy(cfg, w_t, audio, text, n_new, dtype)
+    target, draft = _pair(cfg, w_t, w_d, audio, text, dtype)
     sd = SpecDecoder(target, draft, root=int(text[-1]), threshold=0.05, mode=mode, max_draft=24)   # about a third of the tokens fall below it
+    sd.trace = []
     got = sd.decode(n_new)
     st = sd.stats
+    _check_rounds_against_the_oracle_constructor(sd, mode, 0.05)
     print("%s/%s: %d tokens in %d rounds, %d draft forwards, accepted/round %.2f, nodes/round %.1f, "
           "branch hits %d, recycled %d" % (kind, mode, len(got), st.rounds, st.draft_forwards,
                                            np.mean(st.accepted), np.mean(st.tree_nodes), st.branch_hits, st.recycled))
     stop = _check_lossless(got, want, dec)
-    assert stop == n_new
+    # the fp32 seed was chosen so that all 90 greedy steps are decisive; with bf16 storage a step
+    # may fall inside the (wider) band, and the comparison ends there
+    assert stop == n_new if dtype == "f32" else stop >= 30, stop
     assert len(got) >= n_new and max(st.tree_nodes) <= 64
     assert target.kv_len[0] == draft.kv_len[0] == len(audio) + len(text) - 1 + len(got)
     if kind == "self" and stop == n_new:
@@ -104,5 +150,11 @@ def test_loop_reproduces_the_targets_greedy_decoding(mode, kind):
             assert st.rounds <= n_new // 24 + 2
     if kind == "foreign":
         assert np.mean(st.accepted) < 1.0
+    if kind == "noisy":
+        # partial acceptance: rejected suffixes exist and are reused, and (two-pass tree) some
+        # accepted paths leave the trunk through a second-candidate branch
+        assert st.recycled > 0
+        if mode == "tsp":
+            assert st.branch_hits > 0
     target.close()
     draft.close()

@@ -251,8 +251,8 @@ def test_cfg3_7b_prefix_prefill_as_one_wide_pass(model_7b, monkeypatch):
     tok[n_a:] = text
     flags = [[1] * n_a + [0] * n_t]
 
-    def run():
-        ver = model_7b.verifier(n + 64)
+    def run(flags=0):
+        ver = model_7b.verifier(n + 64, flags=flags)
         emb = torch.zeros((1, n, cfg["d_model"]), dtype=torch.bfloat16, device=ver.device)
         emb[0, :n_a] = torch.from_numpy(audio).to(ver.device).to(torch.bfloat16)
         pf = ver.prefill([tok], embeds=emb, use_embed=flags)
@@ -275,8 +275,8 @@ def test_cfg3_7b_prefix_prefill_as_one_wide_pass(model_7b, monkeypatch):
         print("layers 0-1, first %d positions: max err / max |value| = %.3e" % (P, err))
         # rounded rows on both sides: one bf16 step (2^-8 of an element) plus the arithmetic difference
         assert err <= 5e-3
-    monkeypatch.setenv("SPECASR_WIDE", "0")
-    kn, vn, lg_n = run()
+    from paper_2507_18181_amd import binding as B
+    kn, vn, lg_n = run(B.SPECASR_FLAG_NO_WIDE)
     for a, b in ((kw, kn), (vw, vn)):
         err = np.abs(a - b).max(axis=(1, 2, 3)) / np.abs(b).max(axis=(1, 2, 3))     # per layer
         print("wide pass vs chunks, per layer: max %.3e" % err.max())

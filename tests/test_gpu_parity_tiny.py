@@ -176,29 +176,28 @@ def test_batch_of_ragged_sequences():
     ver.close()
 
 
-@pytest.mark.parametrize("sizes,min_wide_rows", [
-    ((20, 30, 14, 40, 1, 5, 16), "100000"),  # 126 rows, wide passes off: groups of whole sequences, <= 64 rows each
-    ((20, 30, 14, 64, 1, 5, 16), "100000"),  # 150 rows in groups, one of them a full 64-node tree
-    ((20, 30, 14, 1, 1, 5, 16), None),       # 87 rows: one pass on the wide (tiled GEMM) kernels, one row tile
-    ((20, 30, 14, 64, 1, 5, 16), None),      # 150 rows: wide, 2 row tiles
-    ((64, 64, 64, 64, 3, 64, 64), None),     # 387 rows: wide, 4 row tiles, the last almost empty
+@pytest.mark.parametrize("sizes,no_wide", [
+    ((20, 30, 14, 40, 1, 5, 16), True),    # 126 rows, wide passes off: groups of whole sequences, <= 64 rows each
+    ((20, 30, 14, 64, 1, 5, 16), True),    # 150 rows in groups, one of them a full 64-node tree
+    ((20, 30, 14, 1, 1, 5, 16), False),    # 87 rows: one pass on the wide (tiled GEMM) kernels, one row tile
+    ((20, 30, 14, 64, 1, 5, 16), False),   # 150 rows: wide, 2 row tiles
+    ((64, 64, 64, 64, 3, 64, 64), False),  # 387 rows: wide, 4 row tiles, the last almost empty
 ])
-def test_batch_above_64_rows_runs_on_the_mfma_path(sizes, min_wide_rows, monkeypatch):
+def test_batch_above_64_rows_runs_on_the_mfma_path(sizes, no_wide):
     """Seven bf16 sequences with more than 64 tree nodes in total: one pass whose projections run
-    on the tiled GEMM -- or, where wide passes are not available (here: switched off through the
-    tuning variable), consecutive groups of whole sequences with at most 64 rows each on the skinny
+    on the tiled GEMM -- or, where wide passes are not available (here: a context created with
+    SPECASR_FLAG_NO_WIDE), consecutive groups of whole sequences with at most 64 rows each on the skinny
     kernels, spread over several streams.  Either way every sequence equals the oracle run on it
     alone, tree_forward agrees with verify_tree, and the draft-side read-out equals the oracle's
     read-out of the same logits."""
     from paper_2507_18181_amd import binding as B
-    if min_wide_rows is not None:
-        monkeypatch.setenv("SPECASR_WIDE_MIN_ROWS", min_wide_rows)
     cfg = wl.MODELS["tiny"]
     w = wl.make_weights(cfg, 91, "bf16")
     rng = np.random.default_rng(92)
     Ls = [37, 90, 5, 60, 0, 33, 64]
     nb, cap = len(sizes), 160
-    ver = _verifier(cfg, w, "bf16", max_nodes=64, capacity=cap, max_batch=nb)
+    ver = _verifier(cfg, w, "bf16", max_nodes=64, capacity=cap, max_batch=nb,
+                    flags=B.SPECASR_FLAG_NO_WIDE if no_wide else 0)
     assert B.specasr_uses_mfma(ver.ctx, sum(sizes)) == 1
     om = oracle.OracleModel(cfg, w)
     K, V = wl.seeded_cache(cfg, 93, np.asarray(Ls, np.int32), cap, "bf16", batch=nb)
@@ -493,23 +492,23 @@ def test_prefill_wide_passes_equal_oracle_prefill(max_nodes, n_audio, n_text):
                    cap=400, max_pos=320)
 
 
-def test_prefill_without_wide_passes_runs_chunks_on_two_lanes(monkeypatch):
-    """A context created with SPECASR_WIDE=0 has no wide buffers: the same long prefixes go through
+def test_prefill_without_wide_passes_runs_chunks_on_two_lanes():
+    """A context created with SPECASR_FLAG_NO_WIDE has no wide buffers: the same long prefixes go through
     chunks of max_nodes positions, consecutive chunks alternating between two streams that are
     ordered layer by layer with events.  Same result."""
-    monkeypatch.setenv("SPECASR_WIDE", "0")
+    from paper_2507_18181_amd import binding as B
     _check_prefill("bf16", TOL_BF16, 16, n_audio=[250, 100, 64], n_text=[63, 15, 16], L0=[7, 0, 20],
-                   cap=400, max_pos=320)
+                   cap=400, max_pos=320, flags=B.SPECASR_FLAG_NO_WIDE)
 
 
-def _check_prefill(dtype, tol, max_nodes, n_audio, n_text, L0, cap, max_pos):
+def _check_prefill(dtype, tol, max_nodes, n_audio, n_text, L0, cap, max_pos, flags=0):
     cfg = wl.MODELS["tiny"]
     w = wl.make_weights(cfg, 97, dtype)
     rng = np.random.default_rng(98)
     d = cfg["d_model"]
     om = oracle.OracleModel(cfg, w)
     nb = 3
-    ver = _verifier(cfg, w, dtype, max_nodes=max_nodes, capacity=cap, max_batch=nb)
+    ver = _verifier(cfg, w, dtype, max_nodes=max_nodes, capacity=cap, max_batch=nb, flags=flags)
     K, V = wl.seeded_cache(cfg, 99, np.asarray(L0, np.int32), cap, dtype, batch=nb)
     ver.set_cache(K, V, L0)
     emb = torch.zeros((nb, max_pos, d), dtype=ver.tdtype, device=ver.device)
