@@ -9,7 +9,8 @@ import pytest
 
 import oracle
 import workload as wl
-from parity_util import (TOL_BF16, check_forward, check_tree_kv, top2_gap, GAP, widen_cache, row_rel_err,
+from parity_util import (TOL_BF16, check_forward, check_strict_reading, check_tree_kv, top2_gap, GAP, widen_cache,
+                         row_rel_err,
                          check_top2, check_top2_against_oracle_forward)
 
 pytestmark = pytest.mark.gpu
@@ -47,8 +48,10 @@ def model_7b():
     torch.cuda.empty_cache()
 
 
-def _round_checks(ver, om, tokens, parents, L, b=0):
-    """Full verify round of one sequence against the oracle; returns (out, ref)."""
+def _round_checks(ver, om, tokens, parents, L, b=0, strict_bound=TOL_BF16):
+    """Full verify round of one sequence against the oracle, under both readings of what the tree
+    nodes read of each other (rows rounded to the cache's storage type: the guard; unrounded
+    within the pass: `strict_bound`); returns (out, ref)."""
     from paper_2507_18181_amd import binding as B
     n = len(parents)
     k0, v0 = ver.get_cache()
@@ -57,6 +60,7 @@ def _round_checks(ver, om, tokens, parents, L, b=0):
     assert fw["status"] == 0
     lg = fw["logits"][b].cpu().numpy()
     check_forward(ref, lg, fw["argmax"][b].cpu().numpy(), TOL_BF16)
+    check_strict_reading(om, k0[b], v0[b], L, tokens, parents, lg, strict_bound)
     k1, v1 = ver.get_cache()
     check_tree_kv(k1[b], v1[b], L, ref, TOL_BF16)
     assert np.array_equal(k1[b][:, :, :L], k0[b][:, :, :L])
@@ -197,19 +201,21 @@ def test_cfg4_1b_batch16_ragged(model_1b):
     out = ver.verify_tree(toks, trees, want_logits=True)
     assert out["status"] == 0
     k2, v2 = ver.get_cache()
-    for b in (0, 5, 11, 15):          # the oracle recomputes a sample of the sequences one by one
+    order = np.argsort(Ls)
+    strict = {int(order[0]), int(order[Bn // 2]), int(order[-1])}     # shortest, median, longest prefix
+    for b in range(Bn):               # the oracle recomputes every sequence on its own
+        print("sequence %d, prefix %d" % (b, Ls[b]), flush=True)
         ref = model_1b.om.tree_forward(np.ascontiguousarray(K[b]), np.ascontiguousarray(V[b]), int(Ls[b]),
                                        toks[b], trees[b])
         check_forward(ref, out["logits"][b].cpu().numpy(), out["argmax"][b], TOL_BF16)
+        if b in strict:
+            check_strict_reading(model_1b.om, K[b], V[b], int(Ls[b]), toks[b], trees[b], out["logits"][b].cpu().numpy())
         path, alen, nxt = oracle.accept(toks[b], trees[b], out["argmax"][b, :24])
         assert out["accept_len"][b] == alen and out["next_token"][b] == nxt
         assert out["path"][b, :alen].tolist() == path.tolist()
-        want = ref["ktree"][:, :, path]
-        got = widen_cache(k2[b][:, :, Ls[b]:Ls[b] + alen])
-        assert np.abs(got - want).max() <= TOL_BF16 * np.abs(want).max()
-    for b in range(Bn):               # integer stages for every sequence
-        path, alen, nxt = oracle.accept(toks[b], trees[b], out["argmax"][b, :24])
-        assert out["accept_len"][b] == alen and ver.kv_len[b] == Ls[b] + alen
+        sub = {"ktree": ref["ktree"][:, :, path], "vtree": ref["vtree"][:, :, path]}
+        check_tree_kv(k2[b], v2[b], int(Ls[b]), sub, TOL_BF16)      # the committed rows, in path order
+        assert ver.kv_len[b] == Ls[b] + alen
     ver.close()
 
 
@@ -231,15 +237,58 @@ def test_cfg3_7b_32_node_tree(model_7b):
     ver.close()
 
 
-def test_cfg3_7b_prefix_prefill_as_one_wide_pass(model_7b, monkeypatch):
+def test_cfg3_7b_planted_path_leaves_the_trunk(model_7b):
+    """Config 3 at its size with a draft that is partly right: the trunk follows the model's greedy
+    continuation for six tokens, then the model prefers the second candidate, and that branch is
+    right for its four tokens.  The accepted path therefore leaves the trunk, and the in-place
+    compaction really moves rows (branch nodes sit behind all trunk nodes).  The tokens are planted
+    from the GPU's own argmax, level by level; the oracle then checks the final tree as a whole."""
+    spec = wl.WORKLOADS["cfg3_7b_n32"]
+    cfg = model_7b.cfg
+    L = spec["n_audio"] + spec["n_text"]
+    trunk_len, at, depth = 16, 7, 4              # branch = alternative to trunk position 7
+    parents = list(range(-1, trunk_len - 1))     # trunk: nodes 0..15
+    head = len(parents)
+    parents += [at - 1] + list(range(head, head + depth - 1))          # the taken branch: nodes 16..19
+    for p in (3, 10, 13):                                               # three more depth-4 branches, never taken
+        h = len(parents)
+        parents += [p - 1] + list(range(h, h + depth - 1))
+    parents = np.asarray(parents, np.int32)
+    assert len(parents) == 32
+    rng = np.random.default_rng([spec["seed"], 7])
+    tokens = wl.tree_tokens(rng, parents, cfg["vocab"])
+    ver = model_7b.verifier(L + 64)
+    K, V = wl.seeded_cache(cfg, spec["seed"], L, L + 64, "bf16")
+    ver.set_cache(K, V, [L])
+    want_path = list(range(0, at)) + list(range(head, head + depth))    # 0..6, then 16..19
+    for a, b in zip(want_path[:-1], want_path[1:]):                     # plant level by level
+        fw = ver.tree_forward([tokens], [parents], want_logits=False)
+        assert fw["status"] == 0
+        tokens[b] = int(fw["argmax"][0, a])
+        sib = [i for i in range(32) if parents[i] == parents[b] and i != b]
+        for i in sib:                                                   # siblings keep distinct tokens
+            if tokens[i] == tokens[b]:
+                tokens[i] = (tokens[b] + 1) % cfg["vocab"]
+    ver.set_cache(K, V, [L])
+    out, ref = _round_checks(ver, model_7b.om, tokens, parents, L)
+    path = out["path"][0, :out["accept_len"][0]].tolist()
+    print("accepted path", path)
+    # planted from the GPU's own argmax (deterministic kernels), so the walk is fixed whatever the
+    # oracle's gaps are; _round_checks has compared it with the oracle's walk where that is decisive
+    assert path == want_path
+    assert any(v != k for k, v in enumerate(path))                      # rows were moved, not left in place
+    ver.close()
+
+
+def test_cfg3_7b_prefix_prefill_as_one_wide_pass(model_7b):
     """The 810-position prefix of config 3 (750 audio embeddings + 60 prompt tokens) through
     specasr_prefill at the size bench.py --prefill times: ONE pass over 810 rows on the tiled GEMM
     (7 row tiles of 128, the last one with 42 live rows; 13 chain pieces on the shared cache).
     The oracle cannot prefill 32 layers of a 7B model in test time, so it is asked for what it can
-    compute: the K/V rows of layers 0 and 1 at the first 150 positions, which depend on nothing
-    behind them (a 2-layer model on the same weights, prefilled with those positions) -- layer 1
-    has the whole first layer of the pass in front of it (wide GEMMs, finishing kernels, causal
-    attention over two row tiles).  For all 32 layers and all positions the pass is compared with
+    compute: the K/V rows of layers 0 and 1 at ALL 810 positions (a 2-layer model on the same
+    weights, prefilled with the same embeddings and tokens) -- layer 1 has the whole first layer of
+    the pass in front of it (wide GEMMs, finishing kernels, causal attention over all seven row
+    tiles, the ragged last one and the embedding-to-token switch at position 750 included).  For all 32 layers and all positions the pass is compared with
     the library's own chunk-by-chunk prefill on the skinny kernels (the path config 3's verify
     parity covers), and the logits of one more token on top of either cache must agree."""
     cfg, spec = model_7b.cfg, wl.WORKLOADS["cfg3_7b_n32"]
@@ -251,8 +300,8 @@ def test_cfg3_7b_prefix_prefill_as_one_wide_pass(model_7b, monkeypatch):
     tok[n_a:] = text
     flags = [[1] * n_a + [0] * n_t]
 
-    def run(flags=0):
-        ver = model_7b.verifier(n + 64, flags=flags)
+    def run(ctx_flags=0):
+        ver = model_7b.verifier(n + 64, flags=ctx_flags)
         emb = torch.zeros((1, n, cfg["d_model"]), dtype=torch.bfloat16, device=ver.device)
         emb[0, :n_a] = torch.from_numpy(audio).to(ver.device).to(torch.bfloat16)
         pf = ver.prefill([tok], embeds=emb, use_embed=flags)
@@ -265,16 +314,19 @@ def test_cfg3_7b_prefix_prefill_as_one_wide_pass(model_7b, monkeypatch):
         return widen_cache(k[0, :, :, :n]), widen_cache(v[0, :, :, :n]), lg
 
     kw, vw, lg_w = run()
-    P = 150
+    P = n
     om2 = oracle.OracleModel(dict(cfg, n_layers=2), model_7b.w_host)
     kc, vc = om2.empty_cache(P, np.uint16)
-    om2.prefill(kc, vc, 0, audio[:P].astype(np.float64), np.zeros(0, np.int32))
-    for got, want in ((kw, kc), (vw, vc)):
+    om2.prefill(kc, vc, 0, audio.astype(np.float64), text)
+    for name, got, want in (("k", kw, kc), ("v", vw, vc)):
         wv = widen_cache(want)
-        err = np.abs(got[:2, :, :P] - wv).max() / np.abs(wv).max()
-        print("layers 0-1, first %d positions: max err / max |value| = %.3e" % (P, err))
-        # rounded rows on both sides: one bf16 step (2^-8 of an element) plus the arithmetic difference
-        assert err <= 5e-3
+        diff = np.abs(got[:2, :, :P] - wv)
+        rows = diff.max(axis=-1) / np.abs(wv).max(axis=-1)              # per (layer, head, position)
+        last = rows[:, :, 768:].max()
+        print("layers 0-1, %d positions, %s: max row rel err %.3e (last row tile %.3e), mean %.3e"
+              % (P, name, rows.max(), last, diff.mean() / np.abs(wv).mean()))
+        # rounded rows on both sides: one bf16 step of the row's largest element plus the arithmetic difference
+        assert rows.max() <= 2.0 ** -7 + 2e-3
     from paper_2507_18181_amd import binding as B
     kn, vn, lg_n = run(B.SPECASR_FLAG_NO_WIDE)
     for a, b in ((kw, kn), (vw, vn)):
@@ -301,7 +353,8 @@ def test_cfg6_13b_32_node_tree():
     assert B.specasr_uses_mfma(ver.ctx, 32) == 1
     K, V = wl.seeded_cache(m.cfg, spec["seed"], L, L + 64, "bf16")
     ver.set_cache(K, V, [L])
-    _round_checks(ver, m.om, tokens, parents, L)
+    # 13B: under the unrounded reading the error is reported, not bounded (it sits at the edge of 2e-2)
+    _round_checks(ver, m.om, tokens, parents, L, strict_bound=None)
     ver.close()
     del m
     torch.cuda.empty_cache()
@@ -340,6 +393,8 @@ def test_cfg5_7b_long_prefix_64_nodes_20_rounds(model_7b):
             ref = model_7b.om.tree_forward(np.ascontiguousarray(k0[0]), np.ascontiguousarray(v0[0]), Lr,
                                            tokens, parents)
             check_forward(ref, fw["logits"][0].cpu().numpy(), fw["argmax"][0].cpu().numpy(), TOL_BF16)
+            if rnd == 0:
+                check_strict_reading(model_7b.om, k0[0], v0[0], Lr, tokens, parents, fw["logits"][0].cpu().numpy())
             check_tree_kv(k1[0], v1[0], 0, ref, TOL_BF16)
             kf, vf = ver.get_rows(0, Lr)
             assert np.array_equal(kf[0], k0[0][:, :, :Lr]) and np.array_equal(vf[0], v0[0][:, :, :Lr])
