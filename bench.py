@@ -57,6 +57,96 @@ def cpu_baseline(cfg, w_host, kc, vc, kv_len, tokens, parents, reps, draft=False
     return spent / reps, spent, oracle.num_threads()
 
 
+def time_steps(step, n, stream):
+    """Runs step() n times on `stream`, each bracketed by a HIP event pair recorded on that stream
+    (the stream the library is given); returns (wall seconds for all n, per-step event ms)."""
+    import torch
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    outs = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in evs:
+        a.record(stream)
+        outs.append(step())
+        b.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, [a.elapsed_time(b) for a, b in evs], outs
+
+
+def step_stats(ms):
+    import numpy as np
+    a = np.asarray(ms, np.float64)
+    return {"timer": "hipEvent pair per step on the caller's stream", "n": int(a.size),
+            "median_ms": round(float(np.median(a)), 4), "p10_ms": round(float(np.percentile(a, 10)), 4),
+            "p90_ms": round(float(np.percentile(a, 90)), 4), "mean_ms": round(float(a.mean()), 4)}
+
+
+def read_ceiling(ver, log):
+    """Pure read stream over 4 GiB of HBM with the weight stream's access pattern (GB/s)."""
+    import torch
+    from paper_2507_18181_amd import binding as B
+    nbytes = 4 << 30
+    buf = torch.empty(nbytes, dtype=torch.uint8, device=ver.device).fill_(1)
+    torch.cuda.synchronize()
+    rc, gbs = B.specasr_read_ceiling(ver.ctx, buf, nbytes, 5)
+    del buf
+    if rc != 0:
+        log("read ceiling probe failed: status %d" % rc)
+        return None
+    return round(gbs, 1)
+
+
+def bench_rounds(args, spec, cfg, ver, kv_len, stream, log):
+    """The workload's round SEQUENCE (config 5: 20 rounds on one growing cache): every round gets
+    a fresh seeded tree whose root is the previous round's next token, runs the model forward,
+    takes acceptance from seeded logits with planted targets (specasr_accept_from_logits) and
+    commits that path in place.  One untimed pass fixes the inputs (the roots depend on the
+    planted acceptance only); then `repeats` timed passes from the same starting cache."""
+    import numpy as np
+    import torch
+    import workload as wl
+    t, n_rounds, repeats = spec["tree"], spec["rounds"], 5
+    rng = np.random.default_rng([spec["seed"], 2])
+    rounds, root = [], int(rng.integers(0, cfg["vocab"]))
+    ver.kv_len[0] = kv_len
+    for _ in range(n_rounds):
+        parents, _, _ = wl.sparse_tree(rng, t["trunk"], t["n_branches"], t["branch_depth"], t["rule"])
+        tokens = wl.tree_tokens(rng, parents, cfg["vocab"])
+        tokens[0] = root
+        lg = torch.from_numpy(wl.planted_logits(rng, parents, tokens, cfg["vocab"])[None]).to(ver.device)
+        assert ver.tree_forward([tokens], [parents], want_logits=False, stream=stream.cuda_stream)["status"] == 0
+        acc = ver.accept([tokens], [parents], logits_dev=lg, stream=stream.cuda_stream)
+        alen = int(acc["accept_len"][0])
+        path = [int(v) for v in acc["path"][0, :alen]]
+        assert ver.commit([len(parents)], [path], stream=stream.cuda_stream) == 0
+        root = int(acc["next_token"][0])
+        rounds.append((tokens, parents, lg, path))
+    accepted = sum(len(r[3]) for r in rounds)
+    seq_ms, round_ms = [], []
+    for _ in range(repeats):
+        ver.kv_len[0] = kv_len
+
+        def one(r):
+            tokens, parents, lg, path = r
+            ver.tree_forward([tokens], [parents], want_logits=False, stream=stream.cuda_stream)
+            ver.accept([tokens], [parents], logits_dev=lg, stream=stream.cuda_stream)
+            ver.commit([len(parents)], [path], stream=stream.cuda_stream)
+
+        it = iter(rounds)
+        wall, ms, _ = time_steps(lambda: one(next(it)), n_rounds, stream)
+        seq_ms.append(wall * 1e3)
+        round_ms += ms
+    ver.kv_len[0] = kv_len
+    best = float(np.median(seq_ms))
+    return {"rounds": n_rounds, "repeats": repeats, "tree_nodes": len(rounds[0][1]),
+            "accepted_tokens_per_sequence": accepted, "kv_prefix_start": kv_len, "kv_prefix_end": kv_len + accepted,
+            "sequence_ms_median": round(best, 3), "sequence_ms_all": [round(v, 3) for v in seq_ms],
+            "round": step_stats(round_ms), "rounds_per_s": round(n_rounds / (best * 1e-3), 2),
+            "verified_tokens_per_s": round(accepted / (best * 1e-3), 1),
+            "note": "forward + acceptance from seeded planted logits + in-place commit per round"}
+
+
 def bench_prefill(args, spec, cfg, w_host, ver, stage_id, t_gen, log):
     """Times specasr_prefill of the workload's prefix: n_audio seeded audio-embedding rows followed
     by n_text seeded prompt tokens, appended to an empty cache in chain-shaped chunks of 64."""
@@ -74,9 +164,11 @@ def bench_prefill(args, spec, cfg, w_host, ver, stage_id, t_gen, log):
     tok[n_a:] = text
     flags = [[1] * n_a + [0] * n_t]
 
+    stream = torch.cuda.Stream()
+
     def step():
         ver.kv_len[0] = 0
-        out = ver.prefill([tok], embeds=emb, use_embed=flags)
+        out = ver.prefill([tok], embeds=emb, use_embed=flags, stream=stream.cuda_stream)
         assert out["status"] == 0 and ver.kv_len[0] == T
         return out
 
@@ -86,12 +178,7 @@ def bench_prefill(args, spec, cfg, w_host, ver, stage_id, t_gen, log):
         step()
     wide = B.specasr_uses_mfma(ver.ctx, 64) == 1 and T > 64
     assert B.specasr_profile_stage(ver.ctx, stage_id, 2 if wide else 1) == 0
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    dt, step_ms, _ = time_steps(step, steps, stream)
     rc, stage_ms, stage_launches, stage_bytes = B.specasr_stage_time(ver.ctx)
     rc2, stage_rows = B.specasr_stage_rows(ver.ctx)
     B.specasr_profile_stage(ver.ctx, stage_id, False)
@@ -122,6 +209,7 @@ def bench_prefill(args, spec, cfg, w_host, ver, stage_id, t_gen, log):
         "config": {"workload": args.workload + " (prefix prefill)", "model": spec["model"],
                    "audio_positions": n_a, "prompt_tokens": n_t, "chunk": 64,
                    "wide_pass_rows": min(T, 1024) if wide else 0, "batch": 1},
+        "step_time": step_stats(step_ms),
         "roofline": roofline,
         "weights_gen_s": round(t_gen, 1),
     }
@@ -165,9 +253,11 @@ def bench_batch(args, spec, cfg, w_host, w_dev, t_gen, log):
     rows = sum(len(p) for p in trees)
     stage_id = ["qkv", "o", "gate_up", "down", "lm_head"].index(args.stage)
 
+    stream = torch.cuda.Stream()
+
     def step():
         ver.kv_len[:] = Ls
-        out = ver.verify_tree(toks, trees)
+        out = ver.verify_tree(toks, trees, stream=stream.cuda_stream)
         assert out["status"] == 0
         return out
 
@@ -176,12 +266,7 @@ def bench_batch(args, spec, cfg, w_host, w_dev, t_gen, log):
         step()
     wide = rows >= 129
     assert B.specasr_profile_stage(ver.ctx, stage_id, 2 if wide else 1) == 0
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    dt, step_ms, _ = time_steps(step, args.steps, stream)
     rc, stage_ms, stage_launches, stage_bytes = B.specasr_stage_time(ver.ctx)
     rc2, stage_rows = B.specasr_stage_rows(ver.ctx)
     B.specasr_profile_stage(ver.ctx, stage_id, False)
@@ -206,7 +291,7 @@ def bench_batch(args, spec, cfg, w_host, w_dev, t_gen, log):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "model": spec["model"], "batch": Bn, "tree_nodes_total": rows,
                    "kv_prefix_min": int(Ls.min()), "kv_prefix_max": int(Ls.max())},
-        "calls_per_s": round(args.steps / dt, 2),
+        "calls_per_s": round(args.steps / dt, 2), "step_time": step_stats(step_ms),
         "note": "value = utterance verify steps per second (batch x calls/s); ms_per_step is per call",
         "roofline": roofline, "weights_gen_s": round(t_gen, 1),
     }
@@ -273,7 +358,7 @@ def main():
     kv_len = spec["n_audio"] + spec["n_text"]
     parents, tokens = wl.make_tree(args.workload)
     n = len(parents)
-    capacity = kv_len + 64
+    capacity = kv_len + 64 + 30 * spec.get("rounds", 0)      # a round sequence grows the cache
 
     log("generating %s weights on the host" % spec["model"])
     t0 = time.perf_counter()
@@ -298,13 +383,15 @@ def main():
 
     draft = isinstance(spec["tree"], dict) and "two_branch" in spec["tree"]
 
+    stream = torch.cuda.Stream()                       # the caller's stream: library calls and timing events
+
     def step_with(tok):
         ver.kv_len[0] = kv_len
         if draft:                                  # no acceptance on the draft side
-            out = ver.tree_forward_top2([tok], [parents])
+            out = ver.tree_forward_top2([tok], [parents], stream=stream.cuda_stream)
             out["accept_len"] = [0]
         else:
-            out = ver.verify_tree([tok], [parents])
+            out = ver.verify_tree([tok], [parents], stream=stream.cuda_stream)
         assert out["status"] == 0, out["status"]
         return out
 
@@ -323,14 +410,8 @@ def main():
     torch.cuda.synchronize()
     log("timing %d steps" % args.steps)
     assert B.specasr_profile_stage(ver.ctx, stage_id, True) == 0
-    accepted = 0
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        out = step()
-        accepted += int(out["accept_len"][0])
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    dt, step_ms, outs = time_steps(step, args.steps, stream)
+    accepted = sum(int(o["accept_len"][0]) for o in outs)
     rc, stage_ms, stage_launches, stage_bytes = B.specasr_stage_time(ver.ctx)
     assert rc == 0 and stage_launches > 0
     B.specasr_profile_stage(ver.ctx, stage_id, False)
@@ -344,18 +425,14 @@ def main():
         if not kids:
             break
         trunk.append(kids[0])
-    acc2, dt2 = 0, float("nan")
+    acc2, dt2, step2_ms = 0, float("nan"), [float("nan")]
     if not draft:
         for _ in range(len(trunk)):
             o2 = step_with(planted)
             for a, b in zip(trunk[:-1], trunk[1:]):
                 planted[b] = o2["argmax"][0, a]
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        for _ in range(args.steps):
-            acc2 += int(step_with(planted)["accept_len"][0])
-        torch.cuda.synchronize()
-        dt2 = time.perf_counter() - t1
+        dt2, step2_ms, outs2 = time_steps(lambda: step_with(planted), args.steps, stream)
+        acc2 = sum(int(o["accept_len"][0]) for o in outs2)
 
     ms_per_step = dt / args.steps * 1e3
     steps_per_s = args.steps / dt
@@ -364,10 +441,14 @@ def main():
     kern_ms = stage_ms / stage_launches
     kern_gbs = stage_bytes / (kern_ms * 1e-3) / 1e9
 
-    traffic = None
+    # HBM traffic of the dominant kernel comes from rocprofv3 counter runs of this same command,
+    # stored (with the commit they were taken at) under profiles/; it cannot be measured in-process
+    traffic = traffic_src = None
     tfile = os.path.join(ROOT, "profiles", "traffic_%s_%s.json" % (args.stage, args.workload))
     if os.path.exists(tfile):
-        traffic = json.load(open(tfile)).get("hbm_bytes_per_launch")
+        tj = json.load(open(tfile))
+        traffic, traffic_src = tj.get("hbm_bytes_per_launch"), tj.get("source")
+    ceiling = read_ceiling(ver, log)
 
     result = {
         "metric": "draft_tree_forward_steps_per_s" if draft else "tree_verify_steps_per_s",
@@ -379,19 +460,26 @@ def main():
                    "kv_prefix": kv_len, "batch": 1},
         "verified_tokens_per_s": round(accepted / dt, 2),
         "accept_len_mean": round(accepted / args.steps, 3),
+        "step_time": step_stats(step_ms),
         "planted_trunk": None if draft else {"accept_len_mean": round(acc2 / args.steps, 3),
                                              "verified_tokens_per_s": round(acc2 / dt2, 1),
-                                             "ms_per_step": round(dt2 / args.steps * 1e3, 4)},
+                                             "ms_per_step": round(dt2 / args.steps * 1e3, 4),
+                                             "step_time": step_stats(step2_ms)},
         "algorithmic_bytes_per_step": total_bytes,
         "step_hbm_gbs": round(step_gbs, 1), "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4),
+        "read_ceiling_gbs": ceiling,
+        "step_frac_of_read_ceiling": None if not ceiling else round(step_gbs / ceiling, 4),
         "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel (%s projection)" % args.stage,
                      "achieved": round(kern_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(kern_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "launches_timed": stage_launches, "avg_launch_us": round(kern_ms * 1e3, 2),
+                     "traffic_source": traffic_src, "launches_timed": stage_launches, "avg_launch_us": round(kern_ms * 1e3, 2),
                      "bytes_per_launch": stage_bytes},
         "weights_gen_s": round(t_gen, 1),
     }
     log("%.3f ms/step" % ms_per_step)
+    if "rounds" in spec and not draft:
+        log("timing the %d-round sequence" % spec["rounds"])
+        result["round_sequence"] = bench_rounds(args, spec, cfg, ver, kv_len, stream, log)
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample")
         kh, vh = ver.get_cache()

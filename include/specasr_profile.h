@@ -29,6 +29,13 @@ specasr_status specasr_stage_time(specasr_ctx *ctx, double *total_ms, int64_t *l
                                   double *weight_bytes_per_launch);
 specasr_status specasr_stage_rows(specasr_ctx *ctx, int64_t *rows);
 
+/* Measured read ceiling: streams `bytes` (>= 1 MiB, 16-byte aligned DEVICE buffer, read only -- it
+ * should be far larger than the 256 MB Infinity Cache) `reps` times on `stream` with the weight
+ * stream's access pattern and no arithmetic, synchronises, and returns GB/s -- what a benchmark
+ * quotes next to the nominal HBM bandwidth. */
+specasr_status specasr_read_ceiling(specasr_ctx *ctx, const void *buf_dev, size_t bytes, int32_t reps,
+                                    void *stream, double *gb_per_s);
+
 #ifdef __cplusplus
 }
 #endif

@@ -35,7 +35,7 @@ EXPORTS = ("specasr_create", "specasr_destroy", "specasr_workspace_bytes", "spec
            "specasr_accept_from_logits", "specasr_accept_from_logits_static",
            "specasr_commit", "specasr_strerror", "specasr_last_hip_error", "specasr_abi_version",
            "specasr_uses_mfma", "specasr_profile_stage", "specasr_stage_time",
-           "specasr_stage_rows")
+           "specasr_stage_rows", "specasr_read_ceiling")
 SPECASR_STAGE_QKV, SPECASR_STAGE_O, SPECASR_STAGE_GATE_UP, SPECASR_STAGE_DOWN, SPECASR_STAGE_LM_HEAD = range(5)
 
 
@@ -132,6 +132,8 @@ def load_library(path=None):
                                        C.POINTER(C.c_double)]
     lib.specasr_stage_rows.restype = C.c_int
     lib.specasr_stage_rows.argtypes = [vp, C.POINTER(C.c_int64)]
+    lib.specasr_read_ceiling.restype = C.c_int
+    lib.specasr_read_ceiling.argtypes = [vp, vp, C.c_size_t, C.c_int32, vp, C.POINTER(C.c_double)]
     if path is None:
         _lib = lib
     return lib
@@ -220,6 +222,13 @@ def specasr_stage_time(ctx):
     ms, n, b = C.c_double(0), C.c_int64(0), C.c_double(0)
     rc = load_library().specasr_stage_time(ctx, C.byref(ms), C.byref(n), C.byref(b))
     return rc, ms.value, n.value, b.value
+
+
+def specasr_read_ceiling(ctx, buf_dev, nbytes, reps=3, stream=None):
+    """-> (status, GB/s) of a pure read stream over a device buffer."""
+    g = C.c_double(0)
+    rc = load_library().specasr_read_ceiling(ctx, _ptr(buf_dev), nbytes, reps, _ptr(stream), C.byref(g))
+    return rc, g.value
 
 
 def specasr_last_hip_error(ctx):

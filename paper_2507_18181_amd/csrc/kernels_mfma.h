@@ -20,6 +20,7 @@ struct GemmPlan {
   bool wide = false; // many rows: the tiled kernel (only n_splits applies)
 };
 
+void launch_read_probe(const void *buf, size_t bytes, int grid, uint32_t *sink, hipStream_t st);
 void launch_repack(const void *src, int n_out, int K, void *dst, int band0, hipStream_t st);
 hipError_t gemm_skinny_set_lds_limit();
 void launch_gemm_skinny(const PackedMatrix &W, const uint16_t *Xp, int rows, float *part,

@@ -56,6 +56,31 @@ void launch_repack(const void *src, int n_out, int K, void *dst, int band0, hipS
   repack_kernel<<<(unsigned)tiles, 64, 0, st>>>((const uint16_t *)src, n_out, K, (uint16_t *)dst, band0);
 }
 
+// --------------------------------------------------------------------------- read-bandwidth probe
+// Streams `n_vec` 16-byte words with the skinny GEMM's access pattern (one workgroup of 512 threads
+// per compute unit, each wavefront 8 non-temporal loads of 1 KB in flight) and does nothing with
+// them: the ceiling any weight stream on this part can reach, for benchmarks to quote next to the
+// nominal HBM figure.
+__global__ __launch_bounds__(512) void read_probe_kernel(const u32x4 *__restrict__ p, int64_t n_vec, uint32_t *sink) {
+  const int64_t per_wg = (n_vec + gridDim.x - 1) / gridDim.x;
+  const int64_t b0 = per_wg * blockIdx.x, b1 = min(b0 + per_wg, n_vec);
+  u32x4 acc = (u32x4){0u, 0u, 0u, 0u};
+  int64_t i = b0 + threadIdx.x;
+  for (; i + 7 * 512 < b1; i += 8 * 512) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = load_stream(p + i + u * 512);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+  }
+  for (; i < b1; i += 512) acc ^= load_stream(p + i);
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u && n_vec < 0) sink[0] = acc[0];  // never true; keeps the loads
+}
+
+void launch_read_probe(const void *buf, size_t bytes, int grid, uint32_t *sink, hipStream_t st) {
+  read_probe_kernel<<<grid, 512, 0, st>>>((const u32x4 *)buf, (int64_t)(bytes / 16), sink);
+}
+
 // --------------------------------------------------------------------------- skinny GEMM
 // part[s][band][row][o % 32] = sum over k in chunk s of X[row][k] * W[o][k]   (see part_offset)
 // grid.x = P (a multiple of S), block = 512.  Workgroup g: chunk s = g % S, bands g/S + j*(P/S).
