@@ -200,6 +200,10 @@ __global__ __launch_bounds__((512 + 64 * gemm_reducers<NB, LW>())) void gemm_ski
         acc[n][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, xl[k][n]), acc[n][1], 0, 0, 0);
       }
       if (decltype(refill)::value) buf[k] = load_stream(pn + toff[k]);
+      // keep this order in the instruction stream: without the fence the scheduler gathers all
+      // MFMAs of the band behind one wait for ALL its tiles and issues the refills afterwards,
+      // so nothing is in flight while the band is multiplied, reduced and synchronised
+      __builtin_amdgcn_sched_barrier(0);
     }
     float *mine = red + ((unit & 1) * 8 + wave) * (NB * kRedFloats);
 #pragma unroll
@@ -209,6 +213,11 @@ __global__ __launch_bounds__((512 + 64 * gemm_reducers<NB, LW>())) void gemm_ski
     __syncthreads();
     if (NR == 0 && (int)threadIdx.x < NB * 256) sum_and_store(threadIdx.x, unit);
   };
+  // Everything requested so far (first band, activations) has to be there before the first MFMA
+  // anyway.  Stating it here lets the compiler see that inside the loop only the refills are
+  // outstanding, in slot order: it then waits for slot k with "at most LW - 1 younger loads in
+  // flight" instead of draining the whole ring at the top of every band.
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   int unit = 0;
   for (; unit + 1 < n_units; ++unit) do_band(unit, std::true_type{});
   do_band(unit, std::false_type{});
