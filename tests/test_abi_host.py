@@ -202,6 +202,12 @@ def test_measurement_aids_need_the_mfma_path(ctx):
     assert B.specasr_stage_rows(ctx)[0] == B.SPECASR_E_UNSUPPORTED
     assert B.specasr_stage_rows(None)[0] == B.SPECASR_E_NULL
     assert B.specasr_uses_mfma(ctx, 200) == 0
+    # the read-ceiling probe validates its arguments before it touches a GPU
+    assert B.specasr_read_ceiling(None, 0x1000, 1 << 22)[0] == B.SPECASR_E_NULL
+    assert B.specasr_read_ceiling(ctx, None, 1 << 22)[0] == B.SPECASR_E_NULL
+    assert B.specasr_read_ceiling(ctx, 0x1000, 1 << 10)[0] == B.SPECASR_E_UNSUPPORTED      # under 1 MiB
+    assert B.specasr_read_ceiling(ctx, 0x1008, 1 << 22)[0] == B.SPECASR_E_UNSUPPORTED      # not 16-byte aligned
+    assert B.specasr_read_ceiling(ctx, 0x1000, 1 << 22, reps=0)[0] == B.SPECASR_E_UNSUPPORTED
 
 
 def test_static_entry_point_rejects_sizes_beyond_its_device_array(lib):
