@@ -661,3 +661,48 @@ def test_gemm_tiling_edge_shapes_bf16(shape):
         k1, v1 = ver.get_cache()
         check_tree_kv(k1[0], v1[0], L, ref, TOL_BF16)
     ver.close()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_seeded_random_models_and_batches_bf16(seed):
+    """Seeded random draws of everything the kernels' shapes depend on -- width, FFN width, head
+    count and grouping, head size, depth, vocabulary, prefix lengths, batch and tree sizes (so
+    that a call lands on the skinny kernels with one or two row groups or on a wide pass, with
+    single-chunk or chunked attention) -- each a whole verify round per sequence against the oracle
+    run on that sequence alone, integer stages bit-exact."""
+    from paper_2507_18181_amd import binding as B
+    rng = np.random.default_rng([4242, seed])
+    hd = int(rng.choice([64, 128]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    H = Hkv * int(rng.choice([1, 2, 4]))
+    cfg = dict(wl.MODELS["tiny"], n_layers=int(rng.integers(1, 4)), d_model=16 * int(rng.integers(3, 40)),
+               d_ffn=16 * int(rng.integers(3, 70)), n_heads=H, n_kv_heads=Hkv, head_dim=hd,
+               vocab=int(rng.integers(40, 1500)))
+    nb = int(rng.choice([1, 1, 2, 3, 5]))
+    sizes = [int(rng.integers(1, 65)) for _ in range(nb)]
+    Ls = [int(rng.integers(0, 700)) for _ in range(nb)]
+    cap = max(Ls) + 64
+    print("cfg", {k: cfg[k] for k in ("n_layers", "d_model", "d_ffn", "n_heads", "n_kv_heads", "head_dim", "vocab")},
+          "sizes", sizes, "prefixes", Ls, flush=True)
+    w = wl.make_weights(cfg, 4300 + seed, "bf16")
+    om = oracle.OracleModel(cfg, w)
+    ver = _verifier(cfg, w, "bf16", max_nodes=64, capacity=cap, max_batch=nb)
+    assert B.specasr_uses_mfma(ver.ctx, sum(sizes)) == 1
+    K, V = wl.seeded_cache(cfg, 4400 + seed, np.asarray(Ls, np.int32), cap, "bf16", batch=nb)
+    ver.set_cache(K, V, Ls)
+    trees = [wl.random_tree(rng, n, max_children=3) for n in sizes]
+    toks = [wl.tree_tokens(rng, p, cfg["vocab"]) for p in trees]
+    out = ver.verify_tree(toks, trees, want_logits=True)
+    assert out["status"] == 0
+    k2, v2 = ver.get_cache()
+    for b, n in enumerate(sizes):
+        ref = om.tree_forward(np.ascontiguousarray(K[b]), np.ascontiguousarray(V[b]), Ls[b], toks[b], trees[b])
+        check_forward(ref, out["logits"][b].cpu().numpy(), out["argmax"][b], TOL_BF16)
+        path, alen, nxt = oracle.accept(toks[b], trees[b], out["argmax"][b, :n])
+        assert out["accept_len"][b] == alen and out["next_token"][b] == nxt
+        assert out["path"][b, :alen].tolist() == path.tolist()
+        assert ver.kv_len[b] == Ls[b] + alen
+        sub = {"ktree": ref["ktree"][:, :, path], "vtree": ref["vtree"][:, :, path]}
+        check_tree_kv(k2[b], v2[b], Ls[b], sub, TOL_BF16)
+        assert np.array_equal(k2[b][:, :, :Ls[b]], K[b][:, :, :Ls[b]])      # the prefix is untouched
+    ver.close()
