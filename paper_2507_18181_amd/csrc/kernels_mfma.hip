@@ -92,10 +92,12 @@ constexpr int kRedFloats = 16 * kRedStride;     // one wavefront's 32x32 tile
 template <int NB>
 constexpr size_t gemm_lds_bytes() { return (size_t)2 * 8 * NB * kRedFloats * 4; }
 
-// Wavefronts 8.. of a workgroup (NR of them; where the register budget allows any) do nothing but
-// the summation and the stores, so the 8 streaming wavefronts never fall behind one another.
+// Wavefronts 8.. of a workgroup (NR of them; where the register budget allows any: 12 wavefronts
+// are three per SIMD, 170 registers each -- the ring of 12 fits with one accumulator for both
+// activation planes) do nothing but the summation and the stores, so the 8 streaming wavefronts
+// never fall behind one another.
 template <int NB, int LW>
-constexpr int gemm_reducers() { return (NB == 1 && LW <= 8) ? 4 : 0; }
+constexpr int gemm_reducers() { return (NB == 1 && LW <= 12) ? 4 : 0; }
 
 template <int NB, int LW, int STAGE>
 __global__ __launch_bounds__((512 + 64 * gemm_reducers<NB, LW>())) void gemm_skinny_kernel(const u32x4 *__restrict__ Wp,
@@ -184,11 +186,14 @@ __global__ __launch_bounds__((512 + 64 * gemm_reducers<NB, LW>())) void gemm_ski
   auto do_band = [&](int unit, auto refill) {
     const int band = bg + unit * bstride;
     const u32x4 *pn = wbase + (int64_t)(band + bstride) * band_stride;
-    f32x16 acc[NB][2];
+    // hi and lo plane on separate accumulators (independent MFMA chains) where the registers
+    // allow; the ring of 12 with summing wavefronts has one accumulator per row group
+    constexpr int NA = (NB == 1 && LW == 12) ? 1 : 2;
+    f32x16 acc[NB][NA];
 #pragma unroll
     for (int n = 0; n < NB; ++n)
 #pragma unroll
-      for (int h = 0; h < 2; ++h)
+      for (int h = 0; h < NA; ++h)
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[n][h][j] = 0.f;
 #pragma unroll
@@ -197,7 +202,7 @@ __global__ __launch_bounds__((512 + 64 * gemm_reducers<NB, LW>())) void gemm_ski
 #pragma unroll
       for (int n = 0; n < NB; ++n) {
         acc[n][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, xh[k][n]), acc[n][0], 0, 0, 0);
-        acc[n][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, xl[k][n]), acc[n][1], 0, 0, 0);
+        acc[n][NA - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, xl[k][n]), acc[n][NA - 1], 0, 0, 0);
       }
       if (decltype(refill)::value) buf[k] = load_stream(pn + toff[k]);
       // keep this order in the instruction stream: without the fence the scheduler gathers all
@@ -209,7 +214,7 @@ __global__ __launch_bounds__((512 + 64 * gemm_reducers<NB, LW>())) void gemm_ski
 #pragma unroll
     for (int n = 0; n < NB; ++n)
 #pragma unroll
-      for (int j = 0; j < 16; ++j) mine[n * kRedFloats + j * kRedStride + lane] = acc[n][0][j] + acc[n][1][j];
+      for (int j = 0; j < 16; ++j) mine[n * kRedFloats + j * kRedStride + lane] = NA == 2 ? acc[n][0][j] + acc[n][NA - 1][j] : acc[n][0][j];
     __syncthreads();
     if (NR == 0 && (int)threadIdx.x < NB * 256) sum_and_store(threadIdx.x, unit);
   };
