@@ -28,6 +28,13 @@ One round (Sec. IV-A, IV-C, IV-B):
 The draft model runs on the whole current tree at every step (its cost is the weight stream,
 which does not depend on the number of rows), so no draft-side cache state has to be rolled
 back: tree rows live in scratch slots until ``commit``.
+
+Tokens that are appended to the tree behind the last draft forward of a round (the last trunk
+token, recycled tokens, the last level of the branches) have no draft-side K/V row when the
+target accepts them.  No extra forward is spent on them: they stay *pending* and ride in front
+of the next round's tree as a chain (pending tokens -> root -> ...), so that the next round's
+first draft forward computes their rows, and the draft cache is committed one step behind the
+target's: ``draft.kv_len + len(pending) == target.kv_len``.
 """
 import numpy as np
 
@@ -57,6 +64,10 @@ class SpecDecoder:
         self.max_draft, self.threshold, self.mode = max_draft, threshold, mode
         self.max_branches, self.branch_depth, self.recycle = max_branches, branch_depth, recycle
         self.max_nodes = min(target.max_nodes, draft.max_nodes)
+        self.max_pending = 8      # more accepted tokens than this without a draft-side row: catch up at once
+        self.pending = []         # accepted tokens whose draft-side K/V row is still to be computed
+        self._fresh = 0           # nodes of the current tree that the last draft forward covered
+        self._cap = self.max_nodes
         self.kept = {}            # absolute position -> token of the previous round's rejected suffix
         self.stats = RoundStats()
         # Optional recording for tests: set to a list and every round appends a dict with its
@@ -67,12 +78,16 @@ class SpecDecoder:
 
     # -- draft side ---------------------------------------------------------------------------
     def _draft_forward(self, tokens, parents):
-        out = self.d.tree_forward_top2([np.asarray(tokens, np.int32)], [np.asarray(parents, np.int32)])
+        """Draft forward over [pending chain -> tree]; returns the read-out of the tree's nodes."""
+        P = len(self.pending)
+        dt = list(self.pending) + list(tokens)
+        dp = list(range(-1, P - 1)) + [P - 1] + [P + q for q in parents[1:]]
+        out = self.d.tree_forward_top2([np.asarray(dt, np.int32)], [np.asarray(dp, np.int32)])
         if out["status"] != 0:
             raise RuntimeError("draft forward failed: status %d" % out["status"])
         self.stats.draft_forwards += 1
-        self._stale = False                           # every node now has its draft-side K/V row
-        top2, prob = out["top2"][0].cpu().numpy(), out["prob"][0].cpu().numpy()
+        self._fresh = len(tokens)                     # these nodes (and the pending ones) now have a draft-side K/V row
+        top2, prob = out["top2"][0, P:].cpu().numpy(), out["prob"][0, P:].cpu().numpy()
         if self.trace is not None:
             for i in range(len(tokens)):
                 path, j = [], i
@@ -87,15 +102,16 @@ class SpecDecoder:
         pos0 = int(self.t.kv_len[0])                  # absolute position of the root
         tokens, parents, trunk = [self.root], [-1], [0]
         marks = []                                    # (index into trunk, second token, probability)
-        self._stale = True                            # nodes appended since the last draft forward
-        while len(trunk) - 1 < self.max_draft and len(tokens) < self.max_nodes:
+        self._fresh = 0
+        # the pending chain shares the draft model's tree with this round's nodes
+        self._cap = min(self.t.max_nodes, self.d.max_nodes - len(self.pending))
+        while len(trunk) - 1 < self.max_draft and len(tokens) < self._cap:
             top2, prob = self._draft_forward(tokens, parents)
             leaf = trunk[-1]
             t1, t2, p = int(top2[leaf, 0]), int(top2[leaf, 1]), float(prob[leaf])
             tokens.append(t1)
             parents.append(leaf)
             trunk.append(len(tokens) - 1)
-            self._stale = True
             uncertain = p < self.threshold
             if uncertain and self.mode == "tsp" and t2 >= 0:
                 marks.append((len(trunk) - 1, t2, p))
@@ -104,12 +120,11 @@ class SpecDecoder:
             hit = next((q for q in (pos, pos - 1, pos + 1) if self.kept.get(q) == t1), None)
             if self.recycle and hit is not None:
                 q = hit + 1
-                while q in self.kept and len(trunk) - 1 < self.max_draft and len(tokens) < self.max_nodes:
+                while q in self.kept and len(trunk) - 1 < self.max_draft and len(tokens) < self._cap:
                     tokens.append(self.kept[q])
                     parents.append(trunk[-1])
                     trunk.append(len(tokens) - 1)
                     self.stats.recycled += 1
-                    self._stale = True
                     q += 1
                 self.kept = {}
             if uncertain and self.mode == "asp":
@@ -117,28 +132,25 @@ class SpecDecoder:
         self.kept = {}
         if self.mode == "tsp" and marks:
             self._grow_branches(tokens, parents, trunk, marks)
-        if self._stale:
-            self._draft_forward(tokens, parents)
         return tokens, parents, trunk
 
     def _grow_branches(self, tokens, parents, trunk, marks):
         marks = sorted(marks, key=lambda m: m[2])[:self.max_branches]      # least confident first
         open_ = []                                    # [leaf node, depth in branch, trunk index of its first node]
         for k, alt, _ in sorted(marks):
-            if len(tokens) >= self.max_nodes or alt == tokens[trunk[k]]:
+            if len(tokens) >= self._cap or alt == tokens[trunk[k]]:
                 continue
             tokens.append(alt)
             parents.append(trunk[k - 1])
             open_.append([len(tokens) - 1, 1, k])
-            self._stale = True
-        while open_ and len(tokens) < self.max_nodes:
+        while open_ and len(tokens) < self._cap:
             open_ = [b for b in open_ if b[1] < self.branch_depth]
             if not open_:
                 break
             top2, _ = self._draft_forward(tokens, parents)
             still = []
             for leaf, depth, k in open_:
-                if len(tokens) >= self.max_nodes:
+                if len(tokens) >= self._cap:
                     break
                 t1 = int(top2[leaf, 0])
                 pos = k + depth                        # trunk index the next token corresponds to
@@ -147,17 +159,15 @@ class SpecDecoder:
                 if join is not None:                   # concatenate the rest of the trunk, then close
                     node = leaf
                     for q in range(join, len(trunk)):
-                        if depth >= self.branch_depth or len(tokens) >= self.max_nodes:
+                        if depth >= self.branch_depth or len(tokens) >= self._cap:
                             break
                         tokens.append(tokens[trunk[q]])
                         parents.append(node)
                         node = len(tokens) - 1
                         depth += 1
-                        self._stale = True
                     continue
                 tokens.append(t1)
                 parents.append(leaf)
-                self._stale = True
                 still.append([len(tokens) - 1, depth + 1, k])
             open_ = still
 
@@ -176,9 +186,18 @@ class SpecDecoder:
         alen = int(out["accept_len"][0])
         path = [int(v) for v in out["path"][0, :alen]]
         nxt = int(out["next_token"][0])
-        if self.d.commit([n], [path]) != 0:
+        # draft side: commit the pending chain and the accepted nodes the last draft forward covered
+        # (a node appended behind it has no row, nor has anything below it: they form the path's
+        # tail); the tail waits in front of the next round's tree
+        P = len(self.pending)
+        fresh = [v for v in path if v < self._fresh]
+        assert path[:len(fresh)] == fresh
+        if self.d.commit([P + self._fresh], [list(range(P)) + [P + v for v in fresh]]) != 0:
             raise RuntimeError("draft commit failed")
-        assert self.d.kv_len[0] == self.t.kv_len[0] == pos0 + alen
+        self.pending = [tokens[v] for v in path[len(fresh):]]
+        if len(self.pending) > self.max_pending:
+            self._catch_up()
+        assert self.d.kv_len[0] + len(self.pending) == self.t.kv_len[0] == pos0 + alen
         st = self.stats
         st.rounds += 1
         st.accepted.append(alen - 1)
@@ -189,12 +208,21 @@ class SpecDecoder:
         if self.recycle:
             self.kept = {pos0 + i: tokens[trunk[i]] for i in range(alen + 1, len(trunk))}
         if self.trace is not None:
-            self.trace.append(dict(root=tokens[0], pos0=pos0, kept=kept_in, tokens=list(tokens),
+            self.trace.append(dict(root=tokens[0], pos0=pos0, kept=kept_in, max_nodes=self._cap, tokens=list(tokens),
                                    parents=list(parents), trunk=list(trunk), read=self._read,
                                    accept_len=alen, path=path, kept_out=dict(self.kept),
                                    recycled=self.stats.recycled - recycled_before))
         self.root = nxt
         return [tokens[v] for v in path[1:]] + [nxt]
+
+    def _catch_up(self):
+        """One draft forward over the pending tokens alone (a chain), committed at once."""
+        n = len(self.pending)
+        out = self.d.tree_forward_top2([np.asarray(self.pending, np.int32)], [np.arange(-1, n - 1, dtype=np.int32)])
+        if out["status"] != 0 or self.d.commit([n], [list(range(n))]) != 0:
+            raise RuntimeError("draft catch-up failed")
+        self.stats.draft_forwards += 1
+        self.pending = []
 
     def decode(self, n_new):
         """Runs rounds until at least n_new tokens are produced (or the cache is full)."""
